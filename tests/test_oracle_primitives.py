@@ -1,0 +1,121 @@
+"""Pins of the oracle's building blocks against library routines, closed forms and invariants."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+import scipy.special as sps
+
+import oracle
+from oracle import transformer as T
+
+RNG = np.random.default_rng(1234)
+
+
+def test_round_bf16_matches_library_conversion():
+    x32 = (RNG.standard_normal(200000) * np.exp(RNG.uniform(-20, 20, 200000))).astype(np.float32)
+    want = torch.from_numpy(x32).to(torch.bfloat16).to(torch.float64).numpy()
+    got = oracle.round_bf16(x32.astype(np.float64))
+    assert np.array_equal(got, want)
+    # ties go to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert oracle.round_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert oracle.round_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+    # a float64 just above a tie must round up although its float32 image is the tie itself
+    assert oracle.round_bf16(np.array([1.0 + 2.0 ** -8 + 2.0 ** -40]))[0] == 1.0 + 2.0 ** -7
+    assert np.array_equal(oracle.operand(np.array([1.0 + 2.0 ** -8]), "f32"), np.array([1.0 + 2.0 ** -8]))
+
+
+def test_log_softmax_rows_normalise_and_match_library():
+    z = RNG.standard_normal((7, 513)) * 30.0
+    lp = oracle.log_softmax(z)
+    assert np.allclose(np.exp(lp).sum(-1), 1.0, atol=1e-12)
+    assert np.allclose(lp, sps.log_softmax(z, axis=-1), atol=1e-12)
+    # shift invariance and no overflow at huge logits
+    assert np.allclose(oracle.log_softmax(z + 1e4), lp, atol=1e-9)
+
+
+def test_rms_norm():
+    x = RNG.standard_normal((5, 64))
+    g = RNG.standard_normal(64)
+    want = F.rms_norm(torch.from_numpy(x), (64,), torch.from_numpy(g), 1e-6).numpy()
+    assert np.allclose(oracle.rms_norm(x, g, 1e-6), want, atol=1e-13)
+    u = np.sign(RNG.standard_normal((3, 64)))          # rows of +-1 have unit mean square
+    assert np.allclose(oracle.rms_norm(u, np.ones(64), 0.0), u, atol=1e-15)
+
+
+def test_rope_closed_forms():
+    x = RNG.standard_normal((6, 3, 16))
+    pos = np.array([0, 1, 2, 5, 100, 4095])
+    y = oracle.rope(x, pos, 10000.0)
+    assert np.allclose(y[0], x[0], atol=0)                              # position 0: identity
+    assert np.allclose(np.linalg.norm(y, axis=-1), np.linalg.norm(x, axis=-1))   # a rotation
+    # complex form: pair (i, i+hd/2) as a complex number times exp(j * pos * base^(-2i/hd))
+    zc = (x[..., :8] + 1j * x[..., 8:]) * np.exp(1j * pos[:, None, None] * 10000.0 ** (-np.arange(8) / 8.0))
+    assert np.allclose(y[..., :8], zc.real) and np.allclose(y[..., 8:], zc.imag)
+    # head_dim 2: a plain planar rotation by angle pos
+    v = np.array([[[1.0, 0.0]]])
+    r = oracle.rope(v, np.array([0.5]), 10000.0)
+    assert np.allclose(r[0, 0], [np.cos(0.5), np.sin(0.5)])
+    # scores depend on the position difference only
+    q, k = RNG.standard_normal((1, 1, 16)), RNG.standard_normal((1, 1, 16))
+    s1 = (oracle.rope(q, [7], 1e4) * oracle.rope(k, [3], 1e4)).sum()
+    s2 = (oracle.rope(q, [1007], 1e4) * oracle.rope(k, [1003], 1e4)).sum()
+    assert abs(s1 - s2) < 1e-9
+    # base -> infinity leaves all but the first pair untouched
+    yb = oracle.rope(x, pos, 1e300)
+    assert np.allclose(yb[..., 1:8], x[..., 1:8]) and np.allclose(yb[..., 9:], x[..., 9:])
+
+
+def test_swiglu():
+    a = RNG.standard_normal((4, 8))
+    wg, wu, wd = RNG.standard_normal((12, 8)), RNG.standard_normal((12, 8)), RNG.standard_normal((8, 12))
+    ta, tg, tu, td = map(torch.from_numpy, (a, wg, wu, wd))
+    want = ((F.silu(ta @ tg.T) * (ta @ tu.T)) @ td.T).numpy()
+    assert np.allclose(oracle.swiglu_ffn(a, wg, wu, wd, "f32"), want, atol=1e-12)
+    assert np.all(oracle.swiglu_ffn(a, np.zeros_like(wg), wu, wd, "f32") == 0.0)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 2), (6, 1)])
+def test_attention_matches_library_sdpa_and_gqa_mapping(Hq, Hkv):
+    Tq, S, hd = 5, 9, 8
+    q = RNG.standard_normal((Tq, Hq, hd))
+    k = RNG.standard_normal((S, Hkv, hd))
+    v = RNG.standard_normal((S, Hkv, hd))
+    mask = np.concatenate([np.ones((Tq, S - Tq), bool), np.tril(np.ones((Tq, Tq), bool))], 1)
+    got = oracle.attention(q, k, v, mask, "f32").reshape(Tq, Hq, hd)
+    g = Hq // Hkv
+    # library routine, with K/V heads repeated per group by hand (h -> h // g)
+    kr, vr = np.repeat(k, g, axis=1), np.repeat(v, g, axis=1)
+    want = F.scaled_dot_product_attention(
+        torch.from_numpy(q).permute(1, 0, 2)[None], torch.from_numpy(kr).permute(1, 0, 2)[None],
+        torch.from_numpy(vr).permute(1, 0, 2)[None], attn_mask=torch.from_numpy(mask))[0].permute(1, 0, 2).numpy()
+    assert np.allclose(got, want, atol=1e-12)
+    # MHA on the repeated heads is the same thing
+    assert np.allclose(oracle.attention(q, kr, vr, mask, "f32").reshape(Tq, Hq, hd), got, atol=1e-14)
+
+
+def test_attention_zero_query_averages_values():
+    S, hd = 7, 4
+    v = RNG.standard_normal((S, 1, hd))
+    out = oracle.attention(np.zeros((1, 2, hd)), RNG.standard_normal((S, 1, hd)), v, np.ones((1, S), bool), "f32")
+    assert np.allclose(out.reshape(2, hd), v[:, 0].mean(0)[None].repeat(2, 0))
+
+
+def test_attention_bf16_rounds_only_the_softmax_weights():
+    Tq, S, hd = 3, 33, 8
+    q, k, v = RNG.standard_normal((Tq, 1, hd)), RNG.standard_normal((S, 1, hd)), RNG.standard_normal((S, 1, hd))
+    mask = np.ones((Tq, S), bool)
+    s = (q[:, 0] @ k[:, 0].T) / np.sqrt(hd)
+    p = np.exp(s - s.max(-1, keepdims=True))
+    want = (oracle.round_bf16(p) @ v[:, 0]) / p.sum(-1, keepdims=True)
+    assert np.allclose(oracle.attention(q, k, v, mask, "bf16"), want, atol=1e-15)
+
+
+def test_reward_head_is_a_logistic_of_the_normalised_state():
+    class W:
+        def gains(self): return {"final": np.ones(4)}
+        def head(self): return np.array([[1.0, -2.0, 0.5, 0.0]])
+    class D: rms_eps = 0.0; dtype = "f32"
+    h = np.array([[2.0, 2.0, -2.0, 2.0], [0.0, 0.0, 0.0, 4.0]])       # rms = 2 for both rows
+    r = T._reward(D, W(), h)
+    assert np.allclose(r, [1 / (1 + np.exp(1.5)), 0.5])
+    assert np.all((r > 0) & (r < 1))

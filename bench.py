@@ -1,0 +1,158 @@
+"""Benchmark of the SPECS scoring + SubSample step on one MI355X.
+
+A step = score the n candidate blocks of every beam under target, draft and PRM (three
+specs_score_blocks calls) + one specs_subsample, inputs resident in HBM. Prints ONE JSON line:
+candidate tokens scored per second, the roofline of the dominant kernel (timed live with
+events on the launch stream) and the CPU oracle timed on a bounded sample of the same workload.
+
+usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4_7b] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def role_flops(d, M, P_total_rows_ctx, n, L, B):
+    """Algorithmic FLOPs of one scoring pass (GEMMs + attention), for reporting."""
+    qd, kvd = d.n_q_heads * d.head_dim, d.n_kv_heads * d.head_dim
+    per_layer = 2.0 * M * d.d_model * (qd + 2 * kvd) + 2.0 * M * qd * d.d_model + 2.0 * M * d.d_model * 2 * d.ffn \
+        + 2.0 * M * d.ffn * d.d_model
+    attn = 4.0 * d.n_q_heads * d.head_dim * (P_total_rows_ctx + B * n * L * (L + 1) / 2.0)
+    head = 2.0 * M * d.d_model * d.vocab if d.head == "lm" else 2.0 * B * n * d.d_model
+    return d.n_layers * (per_layer + attn) + head
+
+
+def cpu_baseline(wl, budget_layers=2, n_sub=2):
+    """The oracle, untuned, on a bounded sample: n_sub candidates of beam 0 through `budget_layers`
+    layers of each role (prefix keys/values random-filled, as only time is measured) plus the head;
+    scaled linearly to all layers and all candidates."""
+    import dataclasses
+    import numpy as np
+    import oracle
+    from workload.configs import HostWeights
+    P = int(wl.prefix_lens()[0])
+    cand = wl.candidates()[0:1, :n_sub]
+    rng = np.random.default_rng(0)
+    total = 0.0
+    for role, desc in wl.models().items():
+        sub = dataclasses.replace(desc, n_layers=min(budget_layers, desc.n_layers))
+        hw = HostWeights(sub, wl.seed)
+        cached = {l: hw.layer(l) for l in range(sub.n_layers)}
+        head = hw.head()
+        hw.layer = lambda l, c=cached: c[l]
+        hw.head = lambda h=head: h
+        kv = [rng.standard_normal((P, desc.n_kv_heads, desc.head_dim)) for _ in range(sub.n_layers)]
+        cache = oracle.PrefixCache(P, kv, kv, rng.standard_normal(desc.d_model))
+        t0 = time.perf_counter()
+        oracle.forward_sequences(sub, hw, [cand[0]], prefixes=[cache])
+        t_layers = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        if desc.head == "lm":
+            oracle.token_logprob(rng.standard_normal((n_sub * wl.L, desc.d_model)), head, cand[0].reshape(-1))
+        t_head = time.perf_counter() - t0
+        total += (t_layers * desc.n_layers / sub.n_layers + t_head) * (wl.n / n_sub)
+    total *= wl.B
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+    return {"value": wl.B * wl.n * wl.L / total, "unit": "candidate tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"beam 0, {n_sub} of {wl.n} candidates, {budget_layers} layers per role + head, "
+                      f"float64 numpy; scaled linearly to all layers, candidates and beams"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c4_7b")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the one-GPU share of the path; --gpus must be 1 (nothing here uses a second GPU)",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workload as W
+    from paper_2506_15733_amd import synthetic, binding as B
+    wl = W.get_config(args.workload)
+    t_setup = time.time()
+    step = synthetic.ScoringStep(wl, device="cuda:0")
+    step.prefill()
+    torch.cuda.synchronize()
+    print(f"# setup + prefill {time.time() - t_setup:.1f}s", file=sys.stderr, flush=True)
+
+    for _ in range(args.warmup):
+        step.enqueue_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step.enqueue_step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    assert all(v == 0 for v in step.status().values())
+
+    # per-role time with events on the launch stream
+    role_ms = {}
+    for r in step.ROLES:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            step.score(r)
+        e1.record()
+        torch.cuda.synchronize()
+        role_ms[r] = e0.elapsed_time(e1) / 3
+
+    # dominant kernel: the fused gate/up SwiGLU GEMM of the target/PRM model, timed on its own
+    d = wl.target
+    M = wl.B * wl.n * wl.L
+    dm = step.models["target"]
+    A = torch.randn((M, d.d_model), device="cuda:0").to(torch.bfloat16)
+    act = torch.empty((M, d.ffn), dtype=torch.bfloat16, device="cuda:0")
+    wgu = dm.layers[0]["wgu"]
+    reps = 20
+    for _ in range(3):
+        B.specs_op_gate_up(dm.ctx, A, wgu, act)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        B.specs_op_gate_up(dm.ctx, A, wgu, act)
+    e1.record()
+    torch.cuda.synchronize()
+    k_ms = e0.elapsed_time(e1) / reps
+    flops = 2.0 * M * d.d_model * 2 * d.ffn
+    achieved = flops / (k_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(args.workload)
+
+    lens = wl.prefix_lens()
+    ctx_rows = float(sum(int(l) * wl.n * wl.L for l in lens))
+    total_flops = sum(role_flops(m, M, ctx_rows, wl.n, wl.L, wl.B) for m in wl.models().values())
+    line = {
+        "metric": "candidate tokens scored/sec (n blocks x L) on 1 MI355X",
+        "value": M / dt, "unit": "candidate tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if d.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "n": wl.n, "L": wl.L, "prefix_tokens": int(lens.sum()),
+                   "roles": "target+draft+prm+subsample"},
+        "step_tflops": total_flops / dt / 1e12, "step_frac_of_mfma_peak": total_flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "role_ms": role_ms,
+        "roofline": {"kernel": "gemm_mfma_kernel<256, SWIGLU> (gate/up projection + SiLU*mul)", "bound": "mfma",
+                     "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "ms_per_launch": k_ms,
+                     "shape": [M, 2 * d.ffn, d.d_model]},
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

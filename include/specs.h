@@ -1,0 +1,177 @@
+/*
+ * specs.h - C ABI of the SPECS block-scoring + SubSample hot path for AMD MI355X (gfx950).
+ *
+ * The paper's SubSample subroutine (Alg. 2) takes a context tr, n draft blocks Y_1..Y_n, the
+ * target model, the process reward model and the generator, and selects one block with
+ * probability proportional to exp(S_i),
+ *     S_i = log(pi_target(Y_i|tr) / pi_gen(Y_i|tr)) + beta * r(Y_i|tr)               (Eq. 1).
+ * Producing the three ingredients of S_i is one batched forward pass per model over the L
+ * tokens of each block on top of the cached keys/values of tr (Sec. 2, "evaluating a reasoning
+ * block ... computing logits of each token"; appendix "Engineering and Performance
+ * Optimizations": log-probabilities only for the newly generated step, the prefix being a
+ * cache hit). specs_score_blocks is that pass; specs_subsample is the selection.
+ *
+ * Conventions
+ *  - Every tensor pointer is a DEVICE pointer unless the comment says "host". Device memory is
+ *    owned by the caller and only borrowed for the duration of the enqueued work.
+ *  - All work is enqueued on the stream given to specs_ctx_create; calls return without
+ *    synchronising unless stated. The library allocates no device memory: scratch space is
+ *    the caller-provided workspace.
+ *  - Every call returns a specs_status (0 = OK). Nothing throws or aborts. Conditions only
+ *    the device can see (token id out of range, u outside [0,1), non-finite scores) are
+ *    recorded in a device status word read back by specs_ctx_status.
+ *  - Matrices are row-major [out_features, in_features] (y = x W^T), element type given by
+ *    specs_model_desc.dtype (float or bf16). RMSNorm gains are float.
+ *  - Rounding (bf16 models): weights, the normalised input of each projection, Q/K/V after
+ *    the rotary embedding, the un-normalised softmax weights exp(s - max) that multiply V,
+ *    the attention output and the SwiGLU product are bf16; the residual stream, norm
+ *    statistics, attention scores, all accumulators, logits, log-sum-exp, token and block
+ *    log-probabilities and the reward are float.
+ */
+#ifndef SPECS_H
+#define SPECS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct specs_ctx specs_ctx;
+typedef struct specs_model specs_model;
+typedef struct specs_prefix specs_prefix;
+
+typedef enum specs_status {
+  SPECS_OK = 0,
+  SPECS_EINVAL = 1,     /* null pointer, non-positive size, n or L beyond the limits below */
+  SPECS_ESHAPE = 2,     /* model description inconsistent (Hq % Hkv, odd head_dim, ...) */
+  SPECS_ETOKEN = 3,     /* device: a token id outside [0, vocab); the id is clamped, result undefined */
+  SPECS_ERANGE = 4,     /* beta negative or non-finite (host); u outside [0,1) (device) */
+  SPECS_ENONFINITE = 5, /* device: NaN/inf score, or every candidate masked; idx = -1 */
+  SPECS_EHIP = 6,       /* a HIP runtime call failed */
+  SPECS_EWORKSPACE = 7  /* workspace too small for this call */
+} specs_status;
+
+enum { SPECS_F32 = 0, SPECS_BF16 = 1 };
+enum { SPECS_HEAD_LM = 0, SPECS_HEAD_PRM = 1 };
+
+#define SPECS_GATE_UP_GROUP 32   /* interleave granularity of the fused gate/up matrix */
+#define SPECS_MAX_CANDIDATES 1024 /* n limit of specs_subsample */
+#define SPECS_MAX_BETAS 64        /* nb limit of specs_subsample */
+
+/* Decoder-only transformer: pre-norm residual blocks, RMSNorm, rotary embedding with
+ * rotate-half pairing (i, i + head_dim/2) and absolute 0-based positions, grouped-query
+ * attention (query head h reads kv head h / (Hq/Hkv)) with scale 1/sqrt(head_dim), SwiGLU
+ * feed-forward, no biases. head = LM: vocabulary projection; PRM: one scalar row. */
+typedef struct specs_model_desc {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  int32_t dtype;  /* SPECS_F32 | SPECS_BF16: element type of weights, matrix operands and KV cache */
+  int32_t head;   /* SPECS_HEAD_LM | SPECS_HEAD_PRM */
+  float rope_base, rms_eps;
+} specs_model_desc;
+
+typedef struct specs_layer_weights {
+  const void* wqkv;    /* [(Hq + 2 Hkv) * hd, d]: q heads, then k heads, then v heads */
+  const void* wo;      /* [d, Hq * hd] */
+  const void* wgu;     /* [2F, d]: for each group c of 32 FFN units, rows 64c..64c+31 are the gate
+                          rows 32c..32c+31 and rows 64c+32..64c+63 the matching up rows (F % 32 == 0) */
+  const void* wd;      /* [d, F] */
+  const float* g_attn; /* [d] RMSNorm gain before attention */
+  const float* g_ffn;  /* [d] RMSNorm gain before the feed-forward */
+} specs_layer_weights;
+
+typedef struct specs_weights {
+  const void* embed;                  /* [vocab, d] */
+  const void* head;                   /* LM: [vocab, d] (untied); PRM: [d] */
+  const float* g_final;               /* [d] final RMSNorm gain */
+  const specs_layer_weights* layers;  /* HOST array [n_layers] of device pointers (copied by the call) */
+} specs_weights;
+
+/* Bytes of workspace that calls with at most max_rows = B*n*L block tokens (or prefill chunk
+ * rows) over at most max_B prefixes need for this model. Pure host arithmetic. */
+size_t specs_workspace_bytes(const specs_model_desc* desc, int64_t max_rows, int32_t max_B);
+
+/* Context: device ordinal, a hipStream_t (NULL = the default stream) and the caller's workspace
+ * (256-byte aligned). The context keeps no other device memory. */
+int specs_ctx_create(int device, void* hip_stream, void* workspace, size_t workspace_bytes, specs_ctx** out);
+int specs_ctx_destroy(specs_ctx* ctx);
+/* Synchronises the stream, returns the device status word (SPECS_OK or the first device-side
+ * error since the last call of this function) in *device_status and clears it. */
+int specs_ctx_status(specs_ctx* ctx, int* device_status);
+
+/* Wraps the caller's weights (no copy of tensor data; the per-layer pointer table is copied). */
+int specs_model_create(specs_ctx* ctx, const specs_model_desc* desc, const specs_weights* w, specs_model** out);
+int specs_model_destroy(specs_model* m);
+
+/* The cached trace tr of B independent beams for one model: a paged key/value pool
+ *   kv_pool[n_layers][2 (K,V)][num_pages][Hkv][page_tokens][head_dim]   (element type = model dtype;
+ *   keys are stored after the rotary embedding),
+ * a page table page_table[B][max_pages] of physical page numbers (token j of beam b lives in page
+ * page_table[b][j / page_tokens], slot j % page_tokens), the lengths lens[B] (given on host AND on
+ * device) and h_last[B][d]: the float residual-stream output of the last layer at the last prefix
+ * position, which scores the first token of every candidate block. Wraps caller memory; no copy. */
+int specs_prefix_create(specs_ctx* ctx, const specs_model* m, int32_t B, const int32_t* lens_host,
+                        int32_t* lens_dev, int32_t page_tokens, void* kv_pool, int64_t num_pages,
+                        const int32_t* page_table, int32_t max_pages, float* h_last, specs_prefix** out);
+int specs_prefix_destroy(specs_prefix* p);
+
+/* Utility (not part of the timed path): runs the model over the prefix tokens (device, ragged,
+ * beams concatenated in order, sum(lens) ids) and fills the key/value pages and h_last. */
+int specs_prefill(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* prefix_tokens);
+
+/* Batched verification of the candidate blocks of Alg. 1 step II / Alg. 2: cand[B][n][L] token ids.
+ * Every candidate attends to its beam's cached prefix (read once for all n candidates) and
+ * causally to its own block. LM head: out[B][n] = log pi(Y_i | tr) = sum over the L tokens of
+ * log softmax(z)[y_t], and, if tok_logp != NULL, tok_logp[B][n][L] the per-token terms.
+ * PRM head: out[B][n] = sigmoid(w_r . RMSNorm(h)) at the last block token; tok_logp must be NULL.
+ * The prefix is not modified. */
+int specs_score_blocks(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const int32_t* cand,
+                       int32_t n, int32_t L, float* out, float* tok_logp);
+
+/* Appends candidate `chosen[b]` (host array [B]) of the LAST specs_score_blocks call made with this
+ * model and prefix to the cache (Alg. 1 step II, tr <- (tr, Y)): copies its L keys/values into the
+ * pages, sets h_last to its last hidden state and advances lens (host copy inside the handle and
+ * the device array). The page table must already cover lens + L tokens. */
+int specs_commit_block(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* chosen_host);
+
+/* SubSample (Alg. 2) for B beams and nb inverse temperatures at once:
+ *   S_i = logp_target[b][i] - logp_gen[b][i] + beta[j] * reward[b][i]   (Eq. 1; only r is scaled by beta)
+ *   w_i = exp(S_i - max S) for live i (mask[b][i] != 0, NULL = all live: Alg. 2's set L = [n])
+ *   idx[b][j] = min{k : sum_{i<=k} w_i > u[b][j] * sum_i w_i}, in double precision, index order.
+ * beta: host [nb]. u: device double [B][nb], each in [0,1). idx: device int32 [B][nb].
+ * max_reward: device float [B] or NULL; max_i reward[b][i] for the switching test of Alg. 1 step III.
+ * n <= SPECS_MAX_CANDIDATES, nb <= SPECS_MAX_BETAS. */
+int specs_subsample(specs_ctx* ctx, const float* logp_target, const float* logp_gen, const float* reward,
+                    const uint8_t* mask, int32_t B, int32_t n, const float* beta, int32_t nb,
+                    const double* u, int32_t* idx, float* max_reward);
+
+/* ---- Component entry points -------------------------------------------------------------------
+ * The individual contractions of the scoring pass, callable on caller-provided operands so that each
+ * kernel can be verified on its own at full benchmark shapes. dtype = SPECS_F32 | SPECS_BF16 is the
+ * operand element type; accumulation and outputs are float unless stated. They use the context
+ * workspace as scratch (SPECS_EWORKSPACE if it is too small). */
+
+/* C[M][N] = A[M][K] * W[N][K]^T, or C += ... when accumulate != 0 (the residual-stream update). */
+int specs_op_linear(specs_ctx* ctx, int32_t dtype, const void* A, const void* W, int32_t M, int32_t N, int32_t K,
+                    float* C, int32_t accumulate);
+/* act[M][F] (operand dtype) = silu(A Wg^T) * (A Wu^T), Wgu[2F][K] in the interleaved layout of
+ * specs_layer_weights.wgu: the SwiGLU feed-forward's first half. */
+int specs_op_gate_up(specs_ctx* ctx, int32_t dtype, const void* A, const void* Wgu, int32_t M, int32_t F, int32_t K,
+                     void* act);
+/* tok_logp[m] = z[tok[m]] - logsumexp_v z[v], z = A[m] . W[v]: the fused vocabulary head. The [M][V]
+ * logits are never written to memory. */
+int specs_op_lmhead_logprob(specs_ctx* ctx, int32_t dtype, const void* A, const void* W, const int32_t* tok,
+                            int32_t M, int32_t V, int32_t K, float* tok_logp);
+/* Shared-prefix attention of one layer: q[B*n*L][Hq][hd], block keys/values kb, vb[B*n*L][Hkv][hd]
+ * (all operand dtype, after the rotary embedding), prefix keys/values of `layer` from the handle's
+ * pages; out[B*n*L][Hq*hd] (operand dtype). */
+int specs_op_attention(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, int32_t layer, const void* q,
+                       const void* kb, const void* vb, int32_t n, int32_t L, void* out);
+
+const char* specs_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECS_H */

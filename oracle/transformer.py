@@ -52,6 +52,22 @@ def silu(x):
     return x / (1.0 + np.exp(-x))
 
 
+def linear(a, w):
+    """y = a W^T for W stored [out_features, in_features]."""
+    return np.asarray(a, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T
+
+
+def gate_up(a, wg, wu, dtype):
+    """First half of the SwiGLU feed-forward: silu(a Wg^T) * (a Wu^T), rounded as the operand of the down projection."""
+    return operand(silu(linear(a, wg)) * linear(a, wu), dtype)
+
+
+def token_logprob(a, w_head, targets):
+    """log softmax(a W^T)[target] per row: the chain-rule term of one token."""
+    lp = log_softmax(linear(a, w_head))
+    return lp[np.arange(len(targets)), np.asarray(targets)]
+
+
 def swiglu_ffn(a, wg, wu, wd, dtype):
     act = operand(silu(a @ wg.T) * (a @ wu.T), dtype)
     return act @ wd.T

@@ -1,0 +1,93 @@
+// Shared declarations of the HIP implementation (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "specs.h"
+
+typedef __bf16 bf16_t;
+
+// float <-> operand-type conversions. float -> bf16 is round-to-nearest-even (v_cvt_pk_bf16_f32).
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// One scoring (or prefill-chunk) problem as the kernels see it.
+// Row m of the activation matrices is token t of candidate i of beam b: m = (b*n + i)*L + t.
+struct BatchGeom {
+  int B, n, L;              // beams, candidates per beam, block tokens
+  int M;                    // B*n*L
+  int b0;                   // first beam of the prefix handle this launch covers (prefill: one beam at a time)
+  int len_override;         // >= 0: context length used instead of lens[b] (prefill chunks)
+  const int32_t* lens;      // device [B_total]
+  const int32_t* page_table;// device [B_total][max_pages]
+  int max_pages, page_tokens;
+};
+
+struct ModelDims {
+  int d, Hq, Hkv, hd, F, V;
+  float eps, rope_base;
+};
+
+// ---- launchers implemented across the .hip files (all enqueue on `s`) ----
+template <typename T>
+void launch_embed(const int32_t* tok, const T* E, float* x, int M, int d, int V, int* status, hipStream_t s);
+template <typename T>
+void launch_rmsnorm(const float* x, const float* gain, T* out, int M, int d, float eps, hipStream_t s);
+// lm_head operand: row (b,i,t) = norm(t == 0 ? h_last[b0+b] : x[row-1])
+template <typename T>
+void launch_rmsnorm_shifted(const float* x, const float* h_last, const float* gain, T* out, const BatchGeom& g,
+                            int d, float eps, hipStream_t s);
+void launch_rope_table(float* cs, const BatchGeom& g, int hd, float base, hipStream_t s);
+template <typename T>
+void launch_rope_split(const float* qkv, const float* cs, T* q, T* k, T* v, int M, const ModelDims& md, hipStream_t s);
+template <typename T>
+void launch_silu_mul(const float* gu, T* act, int M, int F, hipStream_t s);
+template <typename T>
+void launch_kv_commit(const T* kb, const T* vb, T* poolK, T* poolV, const BatchGeom& g, const ModelDims& md,
+                      int cand_stride_rows, const int32_t* chosen, hipStream_t s);
+template <typename T>
+void launch_prm_head(const float* x, const float* gain, const T* w, float* out, const BatchGeom& g, int d, float eps,
+                     hipStream_t s);
+void launch_copy_rows(const float* x, float* h_last, const BatchGeom& g, int d, const int32_t* chosen, hipStream_t s);
+
+enum GemmEpilogue { EPI_STORE_F32 = 0, EPI_RESIDUAL_ADD = 1 };
+// C[M,N] (float) = A[M,K] * W[N,K]^T, or C += ... (residual add)
+template <typename T>
+void launch_gemm_simple(const T* A, const T* W, float* C, int M, int N, int K, GemmEpilogue epi, hipStream_t s);
+
+template <typename T>
+void launch_attention_simple(const T* q, const T* kb, const T* vb, const T* poolK, const T* poolV, T* out,
+                             const BatchGeom& g, const ModelDims& md, int max_ctx, hipStream_t s);
+
+// Fused vocabulary head: per (row, 64-column tile) partial (max, sum exp) and the target-token logit.
+template <typename T>
+void launch_lmhead_partials_simple(const T* A, const T* W, const int32_t* tok, float* part_max, float* part_sum,
+                                   float* zt, int M, int V, int K, int* n_tiles_out, hipStream_t s);
+int lmhead_simple_tiles(int V);
+void launch_lmhead_merge(const float* part_max, const float* part_sum, const float* zt, int n_tiles, float* tok_logp,
+                         float* block_out, const BatchGeom& g, hipStream_t s);
+
+void launch_subsample(const float* lt, const float* lg, const float* r, const uint8_t* mask, int B, int n,
+                      const float* beta_dev, int nb, const double* u, int32_t* idx, float* max_reward, int* status,
+                      hipStream_t s);
+
+// bf16 MFMA GEMM family (gemm_mfma.hip). Returns false if the shape is not supported.
+enum { MFMA_STORE = 0, MFMA_RESIDUAL = 1, MFMA_SWIGLU = 2, MFMA_LMHEAD = 3 };
+bool launch_gemm_mfma(int epi, const bf16_t* A, const bf16_t* W, int M, int N, int K, float* C, bf16_t* act,
+                      const int32_t* tok, float* part_max, float* part_sum, float* zt, hipStream_t s);
+int mfma_lmhead_tiles(int V);

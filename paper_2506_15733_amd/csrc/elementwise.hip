@@ -1,0 +1,270 @@
+// Bandwidth-bound glue kernels of the scoring pass: embedding gather, RMSNorm, rotary embedding,
+// SiLU*mul, KV-page commit, PRM scalar head, log-softmax merge + block sum.
+#include "common.h"
+
+// ---------------------------------------------------------------- embedding
+template <typename T>
+__global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restrict__ E, float* __restrict__ x, int d,
+                             int V, int* status) {
+  int m = blockIdx.x;
+  int id = tok[m];
+  if (id < 0 || id >= V) {
+    if (threadIdx.x == 0) *status = SPECS_ETOKEN;
+    id = id < 0 ? 0 : V - 1;
+  }
+  const T* row = E + (size_t)id * d;
+  float* xo = x + (size_t)m * d;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) xo[c] = to_f32<T>(row[c]);
+}
+template <typename T>
+void launch_embed(const int32_t* tok, const T* E, float* x, int M, int d, int V, int* status, hipStream_t s) {
+  embed_kernel<T><<<M, 256, 0, s>>>(tok, E, x, d, V, status);
+}
+template void launch_embed<float>(const int32_t*, const float*, float*, int, int, int, int*, hipStream_t);
+template void launch_embed<bf16_t>(const int32_t*, const bf16_t*, float*, int, int, int, int*, hipStream_t);
+
+// ---------------------------------------------------------------- RMSNorm
+// One 256-thread block per row. y = x * rsqrt(mean(x^2) + eps) * gain, float math, output in T.
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+  v = wave_sum(v);
+  int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  float t = red[0] + red[1] + red[2] + red[3];
+  __syncthreads();
+  return t;
+}
+
+template <typename T>
+__device__ __forceinline__ void rmsnorm_row(const float* __restrict__ xr, const float* __restrict__ gain,
+                                            T* __restrict__ yr, int d, float eps, float* red) {
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    float v = xr[c];
+    ss += v * v;
+  }
+  ss = block_sum_256(ss, red);
+  float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int c = threadIdx.x; c < d; c += 256) yr[c] = from_f32<T>(xr[c] * inv * gain[c]);
+}
+
+template <typename T>
+__global__ void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain, T* __restrict__ out, int d,
+                               float eps) {
+  __shared__ float red[4];
+  size_t m = blockIdx.x;
+  rmsnorm_row<T>(x + m * d, gain, out + m * d, d, eps, red);
+}
+template <typename T>
+void launch_rmsnorm(const float* x, const float* gain, T* out, int M, int d, float eps, hipStream_t s) {
+  rmsnorm_kernel<T><<<M, 256, 0, s>>>(x, gain, out, d, eps);
+}
+template void launch_rmsnorm<float>(const float*, const float*, float*, int, int, float, hipStream_t);
+template void launch_rmsnorm<bf16_t>(const float*, const float*, bf16_t*, int, int, float, hipStream_t);
+
+// Operand of the vocabulary head: the hidden state that PRECEDES each scored token.
+template <typename T>
+__global__ void rmsnorm_shifted_kernel(const float* __restrict__ x, const float* __restrict__ h_last,
+                                       const float* __restrict__ gain, T* __restrict__ out, int nL, int L, int b0, int d,
+                                       float eps) {
+  __shared__ float red[4];
+  size_t m = blockIdx.x;
+  int b = (int)(m / nL), t = (int)(m % L);
+  const float* src = (t == 0) ? h_last + (size_t)(b0 + b) * d : x + (m - 1) * d;
+  rmsnorm_row<T>(src, gain, out + m * d, d, eps, red);
+}
+template <typename T>
+void launch_rmsnorm_shifted(const float* x, const float* h_last, const float* gain, T* out, const BatchGeom& g, int d,
+                            float eps, hipStream_t s) {
+  rmsnorm_shifted_kernel<T><<<g.M, 256, 0, s>>>(x, h_last, gain, out, g.n * g.L, g.L, g.b0, d, eps);
+}
+template void launch_rmsnorm_shifted<float>(const float*, const float*, const float*, float*, const BatchGeom&, int,
+                                            float, hipStream_t);
+template void launch_rmsnorm_shifted<bf16_t>(const float*, const float*, const float*, bf16_t*, const BatchGeom&, int,
+                                             float, hipStream_t);
+
+// ---------------------------------------------------------------- rotary embedding
+// cos/sin of pos * base^(-2i/hd), pos = context length + t, evaluated in double so that long
+// contexts lose nothing; one table per call, shared by all layers and heads.
+__global__ void rope_table_kernel(float* __restrict__ cs, int M, int nL, int L, int half, int hd, double base,
+                                  const int32_t* __restrict__ lens, int b0, int len_override) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= M * half) return;
+  int m = idx / half, i = idx % half;
+  int b = m / nL, t = m % L;
+  int ctx = len_override >= 0 ? len_override : lens[b0 + b];
+  double ang = (double)(ctx + t) * pow(base, -2.0 * (double)i / (double)hd);
+  double sn, cn;
+  sincos(ang, &sn, &cn);
+  cs[(size_t)m * hd + i] = (float)cn;
+  cs[(size_t)m * hd + half + i] = (float)sn;
+}
+void launch_rope_table(float* cs, const BatchGeom& g, int hd, float base, hipStream_t s) {
+  int half = hd / 2;
+  int total = g.M * half;
+  rope_table_kernel<<<(total + 255) / 256, 256, 0, s>>>(cs, g.M, g.n * g.L, g.L, half, hd, (double)base, g.lens, g.b0,
+                                                        g.len_override);
+}
+
+// qkv float [M, Hq+2Hkv, hd] -> q T [M,Hq,hd] (rotated), k T [M,Hkv,hd] (rotated), v T [M,Hkv,hd]
+template <typename T>
+__global__ void rope_split_kernel(const float* __restrict__ qkv, const float* __restrict__ cs, T* __restrict__ q,
+                                  T* __restrict__ k, T* __restrict__ v, int Hq, int Hkv, int hd) {
+  size_t m = blockIdx.x;
+  int H = Hq + 2 * Hkv, half = hd / 2;
+  const float* in = qkv + m * (size_t)H * hd;
+  const float* c = cs + m * hd;
+  for (int e = threadIdx.x; e < H * half; e += blockDim.x) {
+    int h = e / half, i = e % half;
+    float x1 = in[h * hd + i], x2 = in[h * hd + half + i];
+    if (h < Hq + Hkv) {
+      float cn = c[i], sn = c[half + i];
+      float y1 = x1 * cn - x2 * sn, y2 = x2 * cn + x1 * sn;
+      T* o = (h < Hq) ? q + (m * Hq + h) * hd : k + (m * Hkv + (h - Hq)) * hd;
+      o[i] = from_f32<T>(y1);
+      o[half + i] = from_f32<T>(y2);
+    } else {
+      T* o = v + (m * Hkv + (h - Hq - Hkv)) * hd;
+      o[i] = from_f32<T>(x1);
+      o[half + i] = from_f32<T>(x2);
+    }
+  }
+}
+template <typename T>
+void launch_rope_split(const float* qkv, const float* cs, T* q, T* k, T* v, int M, const ModelDims& md, hipStream_t s) {
+  rope_split_kernel<T><<<M, 256, 0, s>>>(qkv, cs, q, k, v, md.Hq, md.Hkv, md.hd);
+}
+template void launch_rope_split<float>(const float*, const float*, float*, float*, float*, int, const ModelDims&,
+                                       hipStream_t);
+template void launch_rope_split<bf16_t>(const float*, const float*, bf16_t*, bf16_t*, bf16_t*, int, const ModelDims&,
+                                        hipStream_t);
+
+// ---------------------------------------------------------------- SiLU(gate) * up
+// gu float [M, 2F] in the interleaved-by-32 column order of the fused gate/up matrix.
+template <typename T>
+__global__ void silu_mul_kernel(const float* __restrict__ gu, T* __restrict__ act, int F) {
+  size_t m = blockIdx.x;
+  const float* in = gu + m * 2 * (size_t)F;
+  for (int j = threadIdx.x; j < F; j += blockDim.x) {
+    int col = (j / SPECS_GATE_UP_GROUP) * 2 * SPECS_GATE_UP_GROUP + (j % SPECS_GATE_UP_GROUP);
+    float gte = in[col], up = in[col + SPECS_GATE_UP_GROUP];
+    float sg = gte / (1.0f + expf(-gte));
+    act[m * F + j] = from_f32<T>(sg * up);
+  }
+}
+template <typename T>
+void launch_silu_mul(const float* gu, T* act, int M, int F, hipStream_t s) {
+  silu_mul_kernel<T><<<M, 256, 0, s>>>(gu, act, F);
+}
+template void launch_silu_mul<float>(const float*, float*, int, int, hipStream_t);
+template void launch_silu_mul<bf16_t>(const float*, bf16_t*, int, int, hipStream_t);
+
+// ---------------------------------------------------------------- KV commit into pages
+// Copies L block rows of one candidate per beam (chosen[b], or candidate 0 when chosen == NULL)
+// to positions ctx .. ctx+L-1 of the beam's pages. grid = (L, B), one block per token.
+template <typename T>
+__global__ void kv_commit_kernel(const T* __restrict__ kb, const T* __restrict__ vb, T* __restrict__ poolK,
+                                 T* __restrict__ poolV, BatchGeom g, int Hkv, int hd, const int32_t* __restrict__ chosen) {
+  int t = blockIdx.x, b = blockIdx.y;
+  int i = chosen ? chosen[b] : 0;
+  int ctx = g.len_override >= 0 ? g.len_override : g.lens[g.b0 + b];
+  int pos = ctx + t;
+  int page = g.page_table[(size_t)(g.b0 + b) * g.max_pages + pos / g.page_tokens];
+  int slot = pos % g.page_tokens;
+  size_t m = ((size_t)b * g.n + i) * g.L + t;
+  for (int e = threadIdx.x; e < Hkv * hd; e += blockDim.x) {
+    int h = e / hd, c = e % hd;
+    size_t dst = (((size_t)page * Hkv + h) * g.page_tokens + slot) * hd + c;
+    poolK[dst] = kb[m * Hkv * hd + e];
+    poolV[dst] = vb[m * Hkv * hd + e];
+  }
+}
+template <typename T>
+void launch_kv_commit(const T* kb, const T* vb, T* poolK, T* poolV, const BatchGeom& g, const ModelDims& md,
+                      int /*unused*/, const int32_t* chosen, hipStream_t s) {
+  kv_commit_kernel<T><<<dim3(g.L, g.B), 256, 0, s>>>(kb, vb, poolK, poolV, g, md.Hkv, md.hd, chosen);
+}
+template void launch_kv_commit<float>(const float*, const float*, float*, float*, const BatchGeom&, const ModelDims&,
+                                      int, const int32_t*, hipStream_t);
+template void launch_kv_commit<bf16_t>(const bf16_t*, const bf16_t*, bf16_t*, bf16_t*, const BatchGeom&,
+                                       const ModelDims&, int, const int32_t*, hipStream_t);
+
+// h_last[b0+b] = x[last row of candidate chosen[b] (or 0)]
+__global__ void copy_rows_kernel(const float* __restrict__ x, float* __restrict__ h_last, BatchGeom g, int d,
+                                 const int32_t* __restrict__ chosen) {
+  int b = blockIdx.x;
+  int i = chosen ? chosen[b] : 0;
+  size_t m = ((size_t)b * g.n + i) * g.L + (g.L - 1);
+  for (int c = threadIdx.x; c < d; c += blockDim.x) h_last[(size_t)(g.b0 + b) * d + c] = x[m * d + c];
+}
+void launch_copy_rows(const float* x, float* h_last, const BatchGeom& g, int d, const int32_t* chosen, hipStream_t s) {
+  copy_rows_kernel<<<g.B, 256, 0, s>>>(x, h_last, g, d, chosen);
+}
+
+// ---------------------------------------------------------------- PRM scalar head
+// r[b][i] = sigmoid(w_r . RMSNorm(x at the last block token)), all in float; one block per candidate.
+template <typename T>
+__global__ void prm_head_kernel(const float* __restrict__ x, const float* __restrict__ gain, const T* __restrict__ w,
+                                float* __restrict__ out, int L, int d, float eps) {
+  __shared__ float red[4];
+  size_t c = blockIdx.x;
+  const float* xr = x + (c * L + (L - 1)) * d;
+  float ss = 0.f, dot = 0.f;
+  for (int j = threadIdx.x; j < d; j += 256) {
+    float v = xr[j];
+    ss += v * v;
+    dot += v * gain[j] * to_f32<T>(w[j]);
+  }
+  ss = block_sum_256(ss, red);
+  dot = block_sum_256(dot, red);
+  if (threadIdx.x == 0) {
+    float sc = dot / sqrtf(ss / (float)d + eps);
+    out[c] = 1.0f / (1.0f + expf(-sc));
+  }
+}
+template <typename T>
+void launch_prm_head(const float* x, const float* gain, const T* w, float* out, const BatchGeom& g, int d, float eps,
+                     hipStream_t s) {
+  prm_head_kernel<T><<<g.B * g.n, 256, 0, s>>>(x, gain, w, out, g.L, d, eps);
+}
+template void launch_prm_head<float>(const float*, const float*, const float*, float*, const BatchGeom&, int, float,
+                                     hipStream_t);
+template void launch_prm_head<bf16_t>(const float*, const float*, const bf16_t*, float*, const BatchGeom&, int, float,
+                                      hipStream_t);
+
+// ---------------------------------------------------------------- log-softmax merge + block sum
+// One block of 64*ceil(L/1) ... : grid = B*n blocks, each wave handles rows t = wave, wave+4, ...
+// Row: merge the per-tile (max, sum exp) partials in tile order, tok_logp = z[y] - (max + log sum).
+// Then thread 0 adds the L token terms in index order (fixed order => run-to-run identical).
+__global__ void lmhead_merge_kernel(const float* __restrict__ part_max, const float* __restrict__ part_sum,
+                                    const float* __restrict__ zt, int n_tiles, float* __restrict__ tok_logp,
+                                    float* __restrict__ block_out, int L) {
+  extern __shared__ float lp[];   // [L]
+  size_t c = blockIdx.x;
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int t = wave; t < L; t += 4) {
+    size_t m = c * L + t;
+    const float* pm = part_max + m * n_tiles;
+    const float* ps = part_sum + m * n_tiles;
+    float mx = -INFINITY;
+    for (int j = lane; j < n_tiles; j += 64) mx = fmaxf(mx, pm[j]);
+    mx = wave_max(mx);
+    float sm = 0.f;
+    for (int j = lane; j < n_tiles; j += 64) sm += ps[j] * expf(pm[j] - mx);
+    sm = wave_sum(sm);
+    if (lane == 0) lp[t] = (float)((double)zt[m] - ((double)mx + log((double)sm)));
+  }
+  __syncthreads();
+  if (tok_logp)
+    for (int t = threadIdx.x; t < L; t += blockDim.x) tok_logp[c * L + t] = lp[t];
+  if (threadIdx.x == 0) {
+    double acc = 0.0;   // the block sum reaches ~1e3 in magnitude: add the float terms in double, round once
+    for (int t = 0; t < L; ++t) acc += (double)lp[t];
+    block_out[c] = (float)acc;
+  }
+}
+void launch_lmhead_merge(const float* part_max, const float* part_sum, const float* zt, int n_tiles, float* tok_logp,
+                         float* block_out, const BatchGeom& g, hipStream_t s) {
+  lmhead_merge_kernel<<<g.B * g.n, 256, g.L * sizeof(float), s>>>(part_max, part_sum, zt, n_tiles, tok_logp, block_out,
+                                                                 g.L);
+}

@@ -1,0 +1,519 @@
+// Host side of the C ABI: handle bookkeeping, argument checks, workspace carving and the order
+// in which the kernels of one scoring pass are enqueued. No device memory is allocated here.
+#include "common.h"
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#define HIP_TRY(expr)                    \
+  do {                                   \
+    hipError_t e_ = (expr);              \
+    if (e_ != hipSuccess) return SPECS_EHIP; \
+  } while (0)
+
+static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+static inline size_t esize(int dtype) { return dtype == SPECS_BF16 ? 2 : 4; }
+
+struct specs_model {
+  specs_model_desc desc;
+  specs_weights w;
+  std::vector<specs_layer_weights> layers;
+};
+
+struct specs_prefix {
+  const specs_model* model;
+  int B, page_tokens, max_pages;
+  int64_t num_pages;
+  std::vector<int32_t> lens;
+  int32_t* lens_dev;
+  char* kv_pool;
+  const int32_t* page_table;
+  float* h_last;
+};
+
+// Carved view of the workspace for one (model, rows) pair. Offsets are recomputed per call;
+// nothing but the status word persists between calls except the block keys/values and the
+// final residual stream, which specs_commit_block reads.
+struct Workspace {
+  int* status;
+  float* x;          // [R, d] residual stream (float)
+  char* a;           // [R, max(d, Hq*hd)] operand of the next projection (T)
+  float* qkv;        // [R, (Hq+2Hkv)*hd]
+  char* q;           // [R, Hq*hd] (T)
+  char* attn;        // [R, Hq*hd] (T)
+  char* kblk;        // [n_layers][R, Hkv*hd] (T)
+  char* vblk;
+  float* gu;         // [R, 2F]
+  char* act;         // [R, F] (T)
+  float* cs;         // [R, hd] cos | sin
+  float* part_max;   // [R, tiles]
+  float* part_sum;
+  float* zt;         // [R]
+  int32_t* chosen;   // [B]
+  size_t total;
+};
+
+static Workspace carve(char* base, const specs_model_desc& d, int64_t R, int B) {
+  Workspace w;
+  size_t off = 0, es = esize(d.dtype);
+  auto take = [&](size_t bytes) { char* p = base ? base + off : nullptr; off += align256(bytes); return p; };
+  size_t qd = (size_t)d.n_q_heads * d.head_dim, kvd = (size_t)d.n_kv_heads * d.head_dim;
+  size_t wide = qd > (size_t)d.d_model ? qd : (size_t)d.d_model;
+  w.status = (int*)take(256);
+  w.x = (float*)take(R * d.d_model * 4);
+  w.a = take(R * wide * es);
+  w.qkv = (float*)take(R * (qd + 2 * kvd) * 4);
+  w.q = take(R * qd * es);
+  w.attn = take(R * qd * es);
+  w.kblk = take((size_t)d.n_layers * R * kvd * es);
+  w.vblk = take((size_t)d.n_layers * R * kvd * es);
+  w.gu = (float*)take(R * 2 * (size_t)d.ffn * 4);
+  w.act = take(R * (size_t)d.ffn * es);
+  w.cs = (float*)take(R * d.head_dim * 4);
+  size_t tiles = d.head == SPECS_HEAD_LM ? (size_t)lmhead_simple_tiles(d.vocab) : 1;
+  w.part_max = (float*)take(R * tiles * 4);
+  w.part_sum = (float*)take(R * tiles * 4);
+  w.zt = (float*)take(R * 4);
+  w.chosen = (int32_t*)take((size_t)(B > 0 ? B : 1) * 4);
+  w.total = off;
+  return w;
+}
+
+struct specs_ctx {
+  int device;
+  hipStream_t stream;
+  char* workspace;
+  size_t workspace_bytes;
+  // what the last specs_score_blocks left in the workspace (for specs_commit_block)
+  const specs_model* last_model;
+  const specs_prefix* last_prefix;
+  int last_n, last_L;
+};
+
+static bool desc_ok(const specs_model_desc& d) {
+  if (d.n_layers <= 0 || d.d_model <= 0 || d.n_q_heads <= 0 || d.n_kv_heads <= 0 || d.head_dim <= 0 || d.ffn <= 0 ||
+      d.vocab <= 0)
+    return false;
+  if (d.n_q_heads % d.n_kv_heads) return false;
+  if (d.head_dim % 2) return false;
+  if (d.ffn % SPECS_GATE_UP_GROUP) return false;
+  if (d.dtype != SPECS_F32 && d.dtype != SPECS_BF16) return false;
+  if (d.head != SPECS_HEAD_LM && d.head != SPECS_HEAD_PRM) return false;
+  if (!(d.rope_base > 0.f) || !(d.rms_eps >= 0.f)) return false;
+  return true;
+}
+
+extern "C" size_t specs_workspace_bytes(const specs_model_desc* desc, int64_t max_rows, int32_t max_B) {
+  if (!desc || max_rows <= 0 || max_B <= 0 || !desc_ok(*desc)) return 0;
+  return carve(nullptr, *desc, max_rows, max_B).total;
+}
+
+extern "C" int specs_ctx_create(int device, void* hip_stream, void* workspace, size_t workspace_bytes, specs_ctx** out) {
+  if (!out || !workspace || workspace_bytes < 256 || ((uintptr_t)workspace & 255)) return SPECS_EINVAL;
+  HIP_TRY(hipSetDevice(device));
+  specs_ctx* c = new (std::nothrow) specs_ctx();
+  if (!c) return SPECS_EINVAL;
+  c->device = device;
+  c->stream = (hipStream_t)hip_stream;
+  c->workspace = (char*)workspace;
+  c->workspace_bytes = workspace_bytes;
+  c->last_model = nullptr;
+  c->last_prefix = nullptr;
+  c->last_n = c->last_L = 0;
+  hipError_t e = hipMemsetAsync(workspace, 0, 256, c->stream);   // the status word
+  if (e != hipSuccess) { delete c; return SPECS_EHIP; }
+  *out = c;
+  return SPECS_OK;
+}
+
+extern "C" int specs_ctx_destroy(specs_ctx* ctx) {
+  delete ctx;
+  return SPECS_OK;
+}
+
+extern "C" int specs_ctx_status(specs_ctx* ctx, int* device_status) {
+  if (!ctx || !device_status) return SPECS_EINVAL;
+  int v = 0;
+  HIP_TRY(hipMemcpyAsync(&v, ctx->workspace, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+  HIP_TRY(hipStreamSynchronize(ctx->stream));
+  if (v != 0) {
+    HIP_TRY(hipMemsetAsync(ctx->workspace, 0, sizeof(int), ctx->stream));
+    HIP_TRY(hipStreamSynchronize(ctx->stream));
+  }
+  *device_status = v;
+  return SPECS_OK;
+}
+
+extern "C" int specs_model_create(specs_ctx* ctx, const specs_model_desc* desc, const specs_weights* w, specs_model** out) {
+  if (!ctx || !desc || !w || !out) return SPECS_EINVAL;
+  if (!desc_ok(*desc)) return SPECS_ESHAPE;
+  if (!w->embed || !w->head || !w->g_final || !w->layers) return SPECS_EINVAL;
+  for (int l = 0; l < desc->n_layers; ++l) {
+    const specs_layer_weights& L = w->layers[l];
+    if (!L.wqkv || !L.wo || !L.wgu || !L.wd || !L.g_attn || !L.g_ffn) return SPECS_EINVAL;
+  }
+  specs_model* m = new (std::nothrow) specs_model();
+  if (!m) return SPECS_EINVAL;
+  m->desc = *desc;
+  m->w = *w;
+  m->layers.assign(w->layers, w->layers + desc->n_layers);
+  m->w.layers = m->layers.data();
+  *out = m;
+  return SPECS_OK;
+}
+
+extern "C" int specs_model_destroy(specs_model* m) {
+  delete m;
+  return SPECS_OK;
+}
+
+extern "C" int specs_prefix_create(specs_ctx* ctx, const specs_model* m, int32_t B, const int32_t* lens_host,
+                                   int32_t* lens_dev, int32_t page_tokens, void* kv_pool, int64_t num_pages,
+                                   const int32_t* page_table, int32_t max_pages, float* h_last, specs_prefix** out) {
+  if (!ctx || !m || !lens_host || !lens_dev || !kv_pool || !page_table || !h_last || !out) return SPECS_EINVAL;
+  if (B <= 0 || page_tokens <= 0 || num_pages <= 0 || max_pages <= 0) return SPECS_EINVAL;
+  for (int b = 0; b < B; ++b) {
+    if (lens_host[b] < 0) return SPECS_EINVAL;
+    if ((int64_t)lens_host[b] > (int64_t)max_pages * page_tokens) return SPECS_EINVAL;
+  }
+  specs_prefix* p = new (std::nothrow) specs_prefix();
+  if (!p) return SPECS_EINVAL;
+  p->model = m;
+  p->B = B;
+  p->page_tokens = page_tokens;
+  p->max_pages = max_pages;
+  p->num_pages = num_pages;
+  p->lens.assign(lens_host, lens_host + B);
+  p->lens_dev = lens_dev;
+  p->kv_pool = (char*)kv_pool;
+  p->page_table = page_table;
+  p->h_last = h_last;
+  *out = p;
+  return SPECS_OK;
+}
+
+extern "C" int specs_prefix_destroy(specs_prefix* p) {
+  delete p;
+  return SPECS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+static T* pool_ptr(const specs_prefix* p, const specs_model_desc& d, int layer, int which) {
+  size_t per = (size_t)p->num_pages * d.n_kv_heads * p->page_tokens * d.head_dim;
+  return (T*)p->kv_pool + ((size_t)layer * 2 + which) * per;
+}
+
+static ModelDims dims_of(const specs_model_desc& d) {
+  ModelDims md;
+  md.d = d.d_model; md.Hq = d.n_q_heads; md.Hkv = d.n_kv_heads; md.hd = d.head_dim; md.F = d.ffn; md.V = d.vocab;
+  md.eps = d.rms_eps; md.rope_base = d.rope_base;
+  return md;
+}
+
+template <typename T>
+static void gemm(const T* A, const T* W, float* C, int M, int N, int K, GemmEpilogue epi, hipStream_t s) {
+  launch_gemm_simple<T>(A, W, C, M, N, K, epi, s);
+}
+template <>
+void gemm<bf16_t>(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmEpilogue epi, hipStream_t s) {
+  int e = epi == EPI_RESIDUAL_ADD ? MFMA_RESIDUAL : MFMA_STORE;
+  if (!launch_gemm_mfma(e, A, W, M, N, K, C, nullptr, nullptr, nullptr, nullptr, nullptr, s))
+    launch_gemm_simple<bf16_t>(A, W, C, M, N, K, epi, s);
+}
+
+// act[M,F] = silu(A Wg^T) * (A Wu^T) with Wgu interleaved by 32 rows
+template <typename T>
+static void gate_up(const T* A, const T* Wgu, float* gu, T* act, int M, int F, int K, hipStream_t s) {
+  launch_gemm_simple<T>(A, Wgu, gu, M, 2 * F, K, EPI_STORE_F32, s);
+  launch_silu_mul<T>(gu, act, M, F, s);
+}
+template <>
+void gate_up<bf16_t>(const bf16_t* A, const bf16_t* Wgu, float* gu, bf16_t* act, int M, int F, int K, hipStream_t s) {
+  if (launch_gemm_mfma(MFMA_SWIGLU, A, Wgu, M, 2 * F, K, nullptr, act, nullptr, nullptr, nullptr, nullptr, s)) return;
+  launch_gemm_simple<bf16_t>(A, Wgu, gu, M, 2 * F, K, EPI_STORE_F32, s);
+  launch_silu_mul<bf16_t>(gu, act, M, F, s);
+}
+
+// per-(row, column tile) log-sum-exp partials + target logit; returns the number of column tiles
+template <typename T>
+static int lmhead_partials(const T* A, const T* W, const int32_t* tok, float* pm, float* ps, float* zt, int M, int V,
+                           int K, hipStream_t s) {
+  int tiles = 0;
+  launch_lmhead_partials_simple<T>(A, W, tok, pm, ps, zt, M, V, K, &tiles, s);
+  return tiles;
+}
+template <>
+int lmhead_partials<bf16_t>(const bf16_t* A, const bf16_t* W, const int32_t* tok, float* pm, float* ps, float* zt, int M,
+                            int V, int K, hipStream_t s) {
+  if (launch_gemm_mfma(MFMA_LMHEAD, A, W, M, V, K, nullptr, nullptr, tok, pm, ps, zt, s)) return mfma_lmhead_tiles(V);
+  int tiles = 0;
+  launch_lmhead_partials_simple<bf16_t>(A, W, tok, pm, ps, zt, M, V, K, &tiles, s);
+  return tiles;
+}
+
+template <typename T>
+static void attention(const T* q, const T* kb, const T* vb, const T* pK, const T* pV, T* out, const BatchGeom& g,
+                      const ModelDims& md, int max_ctx, hipStream_t s);
+
+// The trunk over M = B*n*L rows: every row attends to its beam's cached prefix and causally
+// to the earlier rows of its own block. Leaves the final residual stream in ws.x and the
+// per-layer block keys/values in ws.kblk / ws.vblk. commit_pages: also write them into the
+// prefix pages (prefill).
+template <typename T>
+static void run_trunk(const specs_model* m, const specs_prefix* p, const Workspace& ws, const BatchGeom& g,
+                      const int32_t* tokens, int max_ctx, bool commit_pages, int64_t R, hipStream_t s) {
+  const specs_model_desc& d = m->desc;
+  ModelDims md = dims_of(d);
+  int qd = md.Hq * md.hd, kvd = md.Hkv * md.hd;
+  launch_embed<T>(tokens, (const T*)m->w.embed, ws.x, g.M, md.d, md.V, ws.status, s);
+  launch_rope_table(ws.cs, g, md.hd, md.rope_base, s);
+  for (int l = 0; l < d.n_layers; ++l) {
+    const specs_layer_weights& L = m->layers[l];
+    T* kb = (T*)ws.kblk + (size_t)l * R * kvd;
+    T* vb = (T*)ws.vblk + (size_t)l * R * kvd;
+    T* pK = pool_ptr<T>(p, d, l, 0);
+    T* pV = pool_ptr<T>(p, d, l, 1);
+    launch_rmsnorm<T>(ws.x, L.g_attn, (T*)ws.a, g.M, md.d, md.eps, s);
+    gemm<T>((const T*)ws.a, (const T*)L.wqkv, ws.qkv, g.M, qd + 2 * kvd, md.d, EPI_STORE_F32, s);
+    launch_rope_split<T>(ws.qkv, ws.cs, (T*)ws.q, kb, vb, g.M, md, s);
+    attention<T>((const T*)ws.q, kb, vb, pK, pV, (T*)ws.attn, g, md, max_ctx, s);
+    if (commit_pages) launch_kv_commit<T>(kb, vb, pK, pV, g, md, 0, nullptr, s);
+    gemm<T>((const T*)ws.attn, (const T*)L.wo, ws.x, g.M, md.d, qd, EPI_RESIDUAL_ADD, s);
+    launch_rmsnorm<T>(ws.x, L.g_ffn, (T*)ws.a, g.M, md.d, md.eps, s);
+    gate_up<T>((const T*)ws.a, (const T*)L.wgu, ws.gu, (T*)ws.act, g.M, md.F, md.d, s);
+    gemm<T>((const T*)ws.act, (const T*)L.wd, ws.x, g.M, md.d, md.F, EPI_RESIDUAL_ADD, s);
+  }
+}
+
+template <typename T>
+static int score_impl(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const int32_t* cand, int n, int L,
+                      float* out, float* tok_logp) {
+  const specs_model_desc& d = m->desc;
+  int64_t R = (int64_t)p->B * n * L;
+  Workspace ws = carve(ctx->workspace, d, R, p->B);
+  if (ws.total > ctx->workspace_bytes) return SPECS_EWORKSPACE;
+  BatchGeom g;
+  g.B = p->B; g.n = n; g.L = L; g.M = (int)R; g.b0 = 0; g.len_override = -1;
+  g.lens = p->lens_dev; g.page_table = p->page_table; g.max_pages = p->max_pages; g.page_tokens = p->page_tokens;
+  int max_ctx = 0;
+  for (int b = 0; b < p->B; ++b) max_ctx = p->lens[b] > max_ctx ? p->lens[b] : max_ctx;
+  hipStream_t s = ctx->stream;
+  run_trunk<T>(m, p, ws, g, cand, max_ctx, false, R, s);
+  if (d.head == SPECS_HEAD_LM) {
+    launch_rmsnorm_shifted<T>(ws.x, p->h_last, m->w.g_final, (T*)ws.a, g, d.d_model, d.rms_eps, s);
+    int tiles = lmhead_partials<T>((const T*)ws.a, (const T*)m->w.head, cand, ws.part_max, ws.part_sum, ws.zt, g.M,
+                                   d.vocab, d.d_model, s);
+    launch_lmhead_merge(ws.part_max, ws.part_sum, ws.zt, tiles, tok_logp, out, g, s);
+  } else {
+    launch_prm_head<T>(ws.x, m->w.g_final, (const T*)m->w.head, out, g, d.d_model, d.rms_eps, s);
+  }
+  HIP_TRY(hipGetLastError());
+  ctx->last_model = m;
+  ctx->last_prefix = p;
+  ctx->last_n = n;
+  ctx->last_L = L;
+  return SPECS_OK;
+}
+
+extern "C" int specs_score_blocks(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const int32_t* cand,
+                                  int32_t n, int32_t L, float* out, float* tok_logp) {
+  if (!ctx || !m || !p || !cand || !out) return SPECS_EINVAL;
+  if (p->model != m) return SPECS_EINVAL;
+  if (n <= 0 || L <= 0) return SPECS_EINVAL;
+  if (m->desc.head == SPECS_HEAD_PRM && tok_logp) return SPECS_EINVAL;
+  if ((int64_t)p->B * n * L > (int64_t)1 << 30) return SPECS_EINVAL;
+  for (int b = 0; b < p->B; ++b)
+    if (p->lens[b] < 1) return SPECS_EINVAL;       // the first block token is scored from the last prefix position
+  HIP_TRY(hipSetDevice(ctx->device));
+  return m->desc.dtype == SPECS_BF16 ? score_impl<bf16_t>(ctx, m, p, cand, n, L, out, tok_logp)
+                                     : score_impl<float>(ctx, m, p, cand, n, L, out, tok_logp);
+}
+
+template <typename T>
+static int prefill_impl(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* tokens) {
+  const specs_model_desc& d = m->desc;
+  // largest chunk the workspace can hold
+  int64_t maxlen = 0;
+  for (int b = 0; b < p->B; ++b) maxlen = p->lens[b] > maxlen ? p->lens[b] : maxlen;
+  int64_t R = maxlen < 2048 ? maxlen : 2048;
+  while (R > 0 && carve(nullptr, d, R, 1).total > ctx->workspace_bytes) R /= 2;
+  if (R <= 0) return SPECS_EWORKSPACE;
+  Workspace ws = carve(ctx->workspace, d, R, 1);
+  hipStream_t s = ctx->stream;
+  int64_t off = 0;
+  for (int b = 0; b < p->B; ++b) {
+    int len = p->lens[b];
+    for (int c0 = 0; c0 < len; c0 += (int)R) {
+      int rows = len - c0 < R ? len - c0 : (int)R;
+      BatchGeom g;
+      g.B = 1; g.n = 1; g.L = rows; g.M = rows; g.b0 = b; g.len_override = c0;
+      g.lens = p->lens_dev; g.page_table = p->page_table; g.max_pages = p->max_pages; g.page_tokens = p->page_tokens;
+      run_trunk<T>(m, p, ws, g, tokens + off + c0, c0, true, R, s);
+      if (c0 + rows == len) launch_copy_rows(ws.x, p->h_last, g, d.d_model, nullptr, s);
+    }
+    off += len;
+  }
+  HIP_TRY(hipGetLastError());
+  ctx->last_model = nullptr;
+  ctx->last_prefix = nullptr;
+  return SPECS_OK;
+}
+
+extern "C" int specs_prefill(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* prefix_tokens) {
+  if (!ctx || !m || !p || !prefix_tokens) return SPECS_EINVAL;
+  if (p->model != m) return SPECS_EINVAL;
+  HIP_TRY(hipSetDevice(ctx->device));
+  return m->desc.dtype == SPECS_BF16 ? prefill_impl<bf16_t>(ctx, m, p, prefix_tokens)
+                                     : prefill_impl<float>(ctx, m, p, prefix_tokens);
+}
+
+__global__ void advance_lens_kernel(int32_t* lens, int B, int L) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) lens[b] += L;
+}
+
+template <typename T>
+static int commit_impl(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* chosen_host) {
+  const specs_model_desc& d = m->desc;
+  int n = ctx->last_n, L = ctx->last_L;
+  int64_t R = (int64_t)p->B * n * L;
+  Workspace ws = carve(ctx->workspace, d, R, p->B);
+  ModelDims md = dims_of(d);
+  hipStream_t s = ctx->stream;
+  HIP_TRY(hipMemcpyAsync(ws.chosen, chosen_host, sizeof(int32_t) * p->B, hipMemcpyHostToDevice, s));
+  BatchGeom g;
+  g.B = p->B; g.n = n; g.L = L; g.M = (int)R; g.b0 = 0; g.len_override = -1;
+  g.lens = p->lens_dev; g.page_table = p->page_table; g.max_pages = p->max_pages; g.page_tokens = p->page_tokens;
+  size_t kvd = (size_t)md.Hkv * md.hd;
+  for (int l = 0; l < d.n_layers; ++l)
+    launch_kv_commit<T>((const T*)ws.kblk + (size_t)l * R * kvd, (const T*)ws.vblk + (size_t)l * R * kvd,
+                        pool_ptr<T>(p, d, l, 0), pool_ptr<T>(p, d, l, 1), g, md, 0, ws.chosen, s);
+  launch_copy_rows(ws.x, p->h_last, g, d.d_model, ws.chosen, s);
+  advance_lens_kernel<<<(p->B + 63) / 64, 64, 0, s>>>(p->lens_dev, p->B, L);
+  HIP_TRY(hipGetLastError());
+  for (int b = 0; b < p->B; ++b) p->lens[b] += L;
+  ctx->last_model = nullptr;
+  ctx->last_prefix = nullptr;
+  return SPECS_OK;
+}
+
+extern "C" int specs_commit_block(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* chosen_host) {
+  if (!ctx || !m || !p || !chosen_host) return SPECS_EINVAL;
+  if (ctx->last_model != m || ctx->last_prefix != p || ctx->last_L <= 0) return SPECS_EINVAL;
+  for (int b = 0; b < p->B; ++b) {
+    if (chosen_host[b] < 0 || chosen_host[b] >= ctx->last_n) return SPECS_EINVAL;
+    if ((int64_t)p->lens[b] + ctx->last_L > (int64_t)p->max_pages * p->page_tokens) return SPECS_EINVAL;
+  }
+  HIP_TRY(hipSetDevice(ctx->device));
+  return m->desc.dtype == SPECS_BF16 ? commit_impl<bf16_t>(ctx, m, p, chosen_host)
+                                     : commit_impl<float>(ctx, m, p, chosen_host);
+}
+
+extern "C" int specs_subsample(specs_ctx* ctx, const float* logp_target, const float* logp_gen, const float* reward,
+                               const uint8_t* mask, int32_t B, int32_t n, const float* beta, int32_t nb,
+                               const double* u, int32_t* idx, float* max_reward) {
+  if (!ctx || !logp_target || !logp_gen || !reward || !beta || !u || !idx) return SPECS_EINVAL;
+  if (B <= 0 || n <= 0 || nb <= 0 || n > SPECS_MAX_CANDIDATES || nb > SPECS_MAX_BETAS) return SPECS_EINVAL;
+  for (int j = 0; j < nb; ++j)
+    if (!std::isfinite(beta[j]) || beta[j] < 0.f) return SPECS_ERANGE;
+  HIP_TRY(hipSetDevice(ctx->device));
+  launch_subsample(logp_target, logp_gen, reward, mask, B, n, beta, nb, u, idx, max_reward, (int*)ctx->workspace,
+                   ctx->stream);
+  HIP_TRY(hipGetLastError());
+  return SPECS_OK;
+}
+
+// ---------------------------------------------------------------- component entry points
+extern "C" int specs_op_linear(specs_ctx* ctx, int32_t dtype, const void* A, const void* W, int32_t M, int32_t N,
+                               int32_t K, float* C, int32_t accumulate) {
+  if (!ctx || !A || !W || !C || M <= 0 || N <= 0 || K <= 0) return SPECS_EINVAL;
+  if (dtype != SPECS_F32 && dtype != SPECS_BF16) return SPECS_EINVAL;
+  HIP_TRY(hipSetDevice(ctx->device));
+  GemmEpilogue e = accumulate ? EPI_RESIDUAL_ADD : EPI_STORE_F32;
+  if (dtype == SPECS_BF16) gemm<bf16_t>((const bf16_t*)A, (const bf16_t*)W, C, M, N, K, e, ctx->stream);
+  else gemm<float>((const float*)A, (const float*)W, C, M, N, K, e, ctx->stream);
+  HIP_TRY(hipGetLastError());
+  return SPECS_OK;
+}
+
+extern "C" int specs_op_gate_up(specs_ctx* ctx, int32_t dtype, const void* A, const void* Wgu, int32_t M, int32_t F,
+                                int32_t K, void* act) {
+  if (!ctx || !A || !Wgu || !act || M <= 0 || F <= 0 || K <= 0 || F % SPECS_GATE_UP_GROUP) return SPECS_EINVAL;
+  if (dtype != SPECS_F32 && dtype != SPECS_BF16) return SPECS_EINVAL;
+  size_t need = 256 + align256((size_t)M * 2 * F * 4);
+  if (need > ctx->workspace_bytes) return SPECS_EWORKSPACE;
+  float* gu = (float*)(ctx->workspace + 256);
+  HIP_TRY(hipSetDevice(ctx->device));
+  if (dtype == SPECS_BF16) gate_up<bf16_t>((const bf16_t*)A, (const bf16_t*)Wgu, gu, (bf16_t*)act, M, F, K, ctx->stream);
+  else gate_up<float>((const float*)A, (const float*)Wgu, gu, (float*)act, M, F, K, ctx->stream);
+  HIP_TRY(hipGetLastError());
+  ctx->last_model = nullptr;
+  return SPECS_OK;
+}
+
+extern "C" int specs_op_lmhead_logprob(specs_ctx* ctx, int32_t dtype, const void* A, const void* W, const int32_t* tok,
+                                       int32_t M, int32_t V, int32_t K, float* tok_logp) {
+  if (!ctx || !A || !W || !tok || !tok_logp || M <= 0 || V <= 0 || K <= 0) return SPECS_EINVAL;
+  if (dtype != SPECS_F32 && dtype != SPECS_BF16) return SPECS_EINVAL;
+  size_t tiles = (size_t)lmhead_simple_tiles(V);
+  size_t per = align256((size_t)M * tiles * 4);
+  if (256 + 2 * per + align256((size_t)M * 4) > ctx->workspace_bytes) return SPECS_EWORKSPACE;
+  float* pm = (float*)(ctx->workspace + 256);
+  float* ps = (float*)(ctx->workspace + 256 + per);
+  float* zt = (float*)(ctx->workspace + 256 + 2 * per);
+  HIP_TRY(hipSetDevice(ctx->device));
+  int nt = dtype == SPECS_BF16
+               ? lmhead_partials<bf16_t>((const bf16_t*)A, (const bf16_t*)W, tok, pm, ps, zt, M, V, K, ctx->stream)
+               : lmhead_partials<float>((const float*)A, (const float*)W, tok, pm, ps, zt, M, V, K, ctx->stream);
+  BatchGeom g = {};
+  g.B = 1; g.n = M; g.L = 1; g.M = M;
+  launch_lmhead_merge(pm, ps, zt, nt, nullptr, tok_logp, g, ctx->stream);
+  HIP_TRY(hipGetLastError());
+  ctx->last_model = nullptr;
+  return SPECS_OK;
+}
+
+template <typename T>
+static void attention(const T* q, const T* kb, const T* vb, const T* pK, const T* pV, T* out, const BatchGeom& g,
+                      const ModelDims& md, int max_ctx, hipStream_t s) {
+  launch_attention_simple<T>(q, kb, vb, pK, pV, out, g, md, max_ctx, s);
+}
+
+extern "C" int specs_op_attention(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, int32_t layer,
+                                  const void* q, const void* kb, const void* vb, int32_t n, int32_t L, void* out) {
+  if (!ctx || !m || !p || !q || !kb || !vb || !out || n <= 0 || L <= 0) return SPECS_EINVAL;
+  if (p->model != m || layer < 0 || layer >= m->desc.n_layers) return SPECS_EINVAL;
+  const specs_model_desc& d = m->desc;
+  BatchGeom g;
+  g.B = p->B; g.n = n; g.L = L; g.M = p->B * n * L; g.b0 = 0; g.len_override = -1;
+  g.lens = p->lens_dev; g.page_table = p->page_table; g.max_pages = p->max_pages; g.page_tokens = p->page_tokens;
+  int max_ctx = 0;
+  for (int b = 0; b < p->B; ++b) max_ctx = p->lens[b] > max_ctx ? p->lens[b] : max_ctx;
+  ModelDims md = dims_of(d);
+  HIP_TRY(hipSetDevice(ctx->device));
+  if (d.dtype == SPECS_BF16)
+    attention<bf16_t>((const bf16_t*)q, (const bf16_t*)kb, (const bf16_t*)vb, pool_ptr<bf16_t>(p, d, layer, 0),
+                      pool_ptr<bf16_t>(p, d, layer, 1), (bf16_t*)out, g, md, max_ctx, ctx->stream);
+  else
+    attention<float>((const float*)q, (const float*)kb, (const float*)vb, pool_ptr<float>(p, d, layer, 0),
+                     pool_ptr<float>(p, d, layer, 1), (float*)out, g, md, max_ctx, ctx->stream);
+  HIP_TRY(hipGetLastError());
+  return SPECS_OK;
+}
+
+extern "C" const char* specs_strerror(int status) {
+  switch (status) {
+    case SPECS_OK: return "ok";
+    case SPECS_EINVAL: return "invalid argument";
+    case SPECS_ESHAPE: return "inconsistent model description";
+    case SPECS_ETOKEN: return "token id outside the vocabulary";
+    case SPECS_ERANGE: return "beta or uniform outside its range";
+    case SPECS_ENONFINITE: return "non-finite score or no live candidate";
+    case SPECS_EHIP: return "HIP runtime error";
+    case SPECS_EWORKSPACE: return "workspace too small";
+    default: return "unknown status";
+  }
+}

@@ -1,0 +1,130 @@
+"""Device-side set-up of a synthetic scoring step: weights, KV pools, contexts, inputs.
+
+Plumbing for tests, smoke() and bench.py: it draws inputs with the `workload` generators,
+places them in device memory with torch and calls the C ABI through the binding. No arithmetic
+of the method happens here.
+"""
+import numpy as np
+import torch
+
+import workload as W
+from workload.configs import device_tensor, weight_shapes
+from . import binding as B
+
+
+def pack_gate_up(wg, wu):
+    """[F,d],[F,d] -> [2F,d] with gate/up rows interleaved in groups of 32 (layout of specs_layer_weights.wgu)."""
+    F, d = wg.shape
+    g = B.GATE_UP_GROUP
+    return torch.stack([wg.view(F // g, g, d), wu.view(F // g, g, d)], dim=1).reshape(2 * F, d).contiguous()
+
+
+class DeviceModel:
+    """Weights of one model in device memory + its ABI handles (context with own workspace, model)."""
+
+    def __init__(self, desc, device, stream, max_rows, max_B, seed=0):
+        self.desc, self.device = desc, device
+        top, per_layer = weight_shapes(desc)
+        gen = lambda name, shape: device_tensor(desc, seed, name, shape, device)
+        self.embed = gen("embed", top["embed"])
+        self.head = gen("head", top["head"])
+        self.g_final = torch.ones(desc.d_model, dtype=torch.float32, device=device)
+        self.layers = []
+        for l in range(desc.n_layers):
+            wg, wu = gen(f"L{l}/wg", per_layer["wg"]), gen(f"L{l}/wu", per_layer["wu"])
+            self.layers.append(dict(wqkv=gen(f"L{l}/wqkv", per_layer["wqkv"]), wo=gen(f"L{l}/wo", per_layer["wo"]),
+                                    wgu=pack_gate_up(wg, wu), wd=gen(f"L{l}/wd", per_layer["wd"]),
+                                    g_attn=self.g_final, g_ffn=self.g_final))
+            del wg, wu
+        self.cdesc = B.make_desc(desc.n_layers, desc.d_model, desc.n_q_heads, desc.n_kv_heads, desc.head_dim, desc.ffn,
+                                 desc.vocab, desc.dtype, desc.head, desc.rope_base, desc.rms_eps)
+        nbytes = B.specs_workspace_bytes(self.cdesc, max_rows, max_B)
+        assert nbytes > 0
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.ctx = B.specs_ctx_create(torch.device(device).index or 0, stream.cuda_stream, self.workspace)
+        self.model = B.specs_model_create(self.ctx, self.cdesc, self.embed, self.head, self.g_final, self.layers)
+
+    def close(self):
+        B.specs_model_destroy(self.model)
+        B.specs_ctx_destroy(self.ctx)
+
+
+class DevicePrefix:
+    """Paged KV pool, page table, lengths and h_last of B beams for one model."""
+
+    def __init__(self, dm: DeviceModel, lens, page_table, num_pages, page_tokens):
+        d, dev = dm.desc, dm.device
+        tdt = torch.bfloat16 if d.dtype == "bf16" else torch.float32
+        self.kv_pool = torch.zeros((d.n_layers, 2, num_pages, d.n_kv_heads, page_tokens, d.head_dim), dtype=tdt, device=dev)
+        self.page_table = torch.from_numpy(np.ascontiguousarray(page_table)).to(dev)
+        self.lens_host = [int(x) for x in lens]
+        self.lens_dev = torch.tensor(self.lens_host, dtype=torch.int32, device=dev)
+        self.h_last = torch.zeros((len(lens), d.d_model), dtype=torch.float32, device=dev)
+        self.handle = B.specs_prefix_create(dm.ctx, dm.model, self.lens_host, self.lens_dev, page_tokens, self.kv_pool,
+                                            num_pages, self.page_table, self.h_last)
+
+    def close(self):
+        B.specs_prefix_destroy(self.handle)
+
+
+class ScoringStep:
+    """One step of the hot path on a synthetic workload: score the n blocks of every beam under target,
+    draft and PRM, then SubSample per (beam, beta)."""
+
+    ROLES = ("target", "draft", "prm")
+
+    def __init__(self, wl: W.Workload, device="cuda:0", extra_tokens=0, prefill_rows=2048):
+        self.wl, self.device = wl, device
+        torch.cuda.set_device(device)
+        self.stream = torch.cuda.current_stream()
+        lens = wl.prefix_lens()
+        rows = max(wl.B * wl.n * wl.L, min(int(lens.max()), prefill_rows))
+        table, num_pages = wl.page_table(extra_tokens)
+        self.models, self.prefixes = {}, {}
+        for role, desc in wl.models().items():
+            self.models[role] = DeviceModel(desc, device, self.stream, rows, wl.B, wl.seed)
+            self.prefixes[role] = DevicePrefix(self.models[role], lens, table, num_pages, wl.page_tokens)
+        self.cand = torch.from_numpy(wl.candidates()).to(device)
+        self.prefix_tokens = torch.from_numpy(np.concatenate(wl.prefix_tokens()).astype(np.int32)).to(device)
+        self.u = torch.from_numpy(wl.uniforms()).to(device)
+        f = lambda *s: torch.zeros(s, dtype=torch.float32, device=device)
+        self.out = {r: f(wl.B, wl.n) for r in self.ROLES}
+        self.tok = {r: f(wl.B, wl.n, wl.L) for r in ("target", "draft")}
+        self.idx = torch.zeros((wl.B, len(wl.betas)), dtype=torch.int32, device=device)
+        self.max_reward = f(wl.B)
+
+    def prefill(self):
+        for r in self.ROLES:
+            B.specs_prefill(self.models[r].ctx, self.models[r].model, self.prefixes[r].handle, self.prefix_tokens)
+
+    def score(self, role, cand=None, out=None, tok=None):
+        dm = self.models[role]
+        B.specs_score_blocks(dm.ctx, dm.model, self.prefixes[role].handle, self.cand if cand is None else cand,
+                             self.out[role] if out is None else out,
+                             (self.tok.get(role) if tok is None else tok))
+
+    def enqueue_step(self):
+        for r in self.ROLES:
+            self.score(r)
+        B.specs_subsample(self.models["target"].ctx, self.out["target"], self.out["draft"], self.out["prm"],
+                          self.wl.betas, self.u, self.idx, None, self.max_reward)
+
+    def status(self):
+        return {r: B.specs_ctx_status(self.models[r].ctx) for r in self.ROLES}
+
+    def score_and_select(self):
+        self.enqueue_step()
+        torch.cuda.synchronize()
+        st = self.status()
+        assert all(v == 0 for v in st.values()), st
+        res = {r: self.out[r].cpu().numpy() for r in self.ROLES}
+        res["tok_target"] = self.tok["target"].cpu().numpy()
+        res["tok_draft"] = self.tok["draft"].cpu().numpy()
+        res["idx"] = self.idx.cpu().numpy()
+        res["max_reward"] = self.max_reward.cpu().numpy()
+        return res
+
+    def close(self):
+        for r in self.ROLES:
+            self.prefixes[r].close()
+            self.models[r].close()

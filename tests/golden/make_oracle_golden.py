@@ -1,0 +1,61 @@
+"""Writes tests/golden/oracle_<config>.json: the CPU oracle's outputs on a seeded benchmark configuration.
+
+Calls only `oracle` (and the input generators in `workload`); nothing here touches the HIP path.
+The large configurations take minutes (c3) to an hour (c4) of float64 BLAS time, which is why
+their expected values are stored instead of being recomputed inside the GPU test run.
+
+usage: python tests/golden/make_oracle_golden.py c3_1p5b [--beams 0,1]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+import oracle  # noqa: E402
+import workload as W  # noqa: E402
+from workload.configs import HostWeights  # noqa: E402
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("config")
+    ap.add_argument("--beams", default=None, help="comma-separated beam indices (default: all)")
+    ap.add_argument("--roles", default="target,draft,prm")
+    args = ap.parse_args()
+    wl = W.get_config(args.config)
+    beams = list(range(wl.B)) if args.beams is None else [int(b) for b in args.beams.split(",")]
+    pt_all, cand_all = wl.prefix_tokens(), wl.candidates()
+    pt, cand = [pt_all[b] for b in beams], cand_all[beams]
+    out = {"config": args.config, "beams": beams, "seed": wl.seed,
+           "note": "float64 oracle, cached mode (proved equal to full recompute in tests/test_oracle_scoring.py)"}
+    path = os.path.join(ROOT, "tests", "golden", f"oracle_{args.config}.json")
+    if os.path.exists(path):
+        old = json.load(open(path))
+        if old.get("beams") == beams:
+            out.update({k: v for k, v in old.items() if k not in out})
+    for role in args.roles.split(","):
+        desc = wl.models()[role]
+        t0 = time.time()
+        hw = HostWeights(desc, wl.seed)
+        caches = oracle.prefill(desc, hw, pt)
+        t1 = time.time()
+        res = oracle.score_cached(desc, hw, caches, cand)
+        t2 = time.time()
+        if desc.head == "prm":
+            out[role] = np.asarray(res).tolist()
+        else:
+            out[role] = res[0].tolist()
+            out["tok_" + role] = res[1].tolist()
+        out[f"seconds_{role}"] = {"prefill": round(t1 - t0, 1), "score": round(t2 - t1, 1)}
+        print(role, out[f"seconds_{role}"], flush=True)
+        json.dump(out, open(path, "w"))
+    print("wrote", path)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,181 @@
+"""Each contraction kernel on its own against the oracle's definition, on identical operands
+(bf16 inputs are exactly representable on both sides, so only accumulation order differs).
+Shapes span several tiles with ragged tails, plus the 7B-class benchmark shapes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workload as W
+from workload.configs import ModelDesc, HostWeights
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2506_15733_amd import binding as B
+    ws = torch.zeros(3 << 30, dtype=torch.uint8, device=DEV)
+    c = B.specs_ctx_create(0, torch.cuda.current_stream().cuda_stream, ws)
+    yield c
+    B.specs_ctx_destroy(c)
+
+
+def draw(name, shape, std=1.0, dtype="bf16"):
+    a = W.rng.normal_tensor(7, name, shape, std, dtype)
+    t = torch.from_numpy(a).to(DEV)
+    return a, (t.to(torch.bfloat16) if dtype == "bf16" else t)
+
+
+def close(got, want, rel):
+    scale = np.sqrt((want ** 2).mean()) + 1e-30
+    err = np.abs(got - want).max() / scale
+    assert err < rel, err
+    return err
+
+
+LINEAR_SHAPES = [(45, 100, 64), (256, 256, 64), (300, 1152, 128), (130, 257, 192), (2048, 4608, 3584),
+                 (1024, 1536, 8960), (256, 1024, 2816), (2048, 3584, 18944)]
+
+
+@pytest.mark.parametrize("M,N,K", LINEAR_SHAPES)
+def test_linear_bf16(ctx, M, N, K):
+    from paper_2506_15733_amd import binding as B
+    a, ta = draw(f"a{M}.{K}", (M, K))
+    w, tw = draw(f"w{N}.{K}", (N, K), 0.02)
+    c0, _ = draw(f"c{M}.{N}", (M, N), 1.0, "f32")
+    out = torch.from_numpy(c0).to(DEV)
+    B.specs_op_linear(ctx, ta, tw, out, accumulate=False)
+    torch.cuda.synchronize()
+    want = oracle.linear(a, w)
+    close(out.cpu().numpy().astype(np.float64), want, 2e-5)
+    out = torch.from_numpy(c0).to(DEV)
+    B.specs_op_linear(ctx, ta, tw, out, accumulate=True)
+    torch.cuda.synchronize()
+    close(out.cpu().numpy().astype(np.float64), want + c0, 2e-5)
+
+
+def test_linear_f32(ctx):
+    from paper_2506_15733_amd import binding as B
+    a, ta = draw("fa", (70, 100), 1.0, "f32")
+    w, tw = draw("fw", (130, 100), 0.05, "f32")
+    out = torch.zeros((70, 130), dtype=torch.float32, device=DEV)
+    B.specs_op_linear(ctx, ta, tw, out)
+    torch.cuda.synchronize()
+    close(out.cpu().numpy().astype(np.float64), oracle.linear(a, w), 2e-6)
+
+
+@pytest.mark.parametrize("M,F,K", [(45, 96, 64), (300, 160, 128), (256, 2816, 1024), (2048, 18944, 3584)])
+def test_gate_up_bf16(ctx, M, F, K):
+    from paper_2506_15733_amd import binding as B
+    from paper_2506_15733_amd.synthetic import pack_gate_up
+    a, ta = draw(f"ga{M}.{K}", (M, K))
+    wg, tg = draw(f"wg{F}.{K}", (F, K), 0.02)
+    wu, tu = draw(f"wu{F}.{K}", (F, K), 0.02)
+    act = torch.zeros((M, F), dtype=torch.bfloat16, device=DEV)
+    B.specs_op_gate_up(ctx, ta, pack_gate_up(tg, tu), act)
+    torch.cuda.synchronize()
+    got = act.float().cpu().numpy().astype(np.float64)
+    exact = oracle.silu(oracle.linear(a, wg)) * oracle.linear(a, wu)
+    want = oracle.round_bf16(exact)
+    # identical except where float accumulation order moves a value across a bf16 rounding boundary
+    ulp = np.abs(want) * 2.0 ** -7 + 1e-30
+    assert np.all(np.abs(got - want) <= ulp)
+    assert (got != want).mean() < 2e-3
+    close(got, exact, 4e-3)
+
+
+@pytest.mark.parametrize("M,V,K", [(45, 301, 64), (100, 1000, 128), (256, 32768, 1024), (512, 152064, 3584)])
+def test_lmhead_logprob_bf16(ctx, M, V, K):
+    from paper_2506_15733_amd import binding as B
+    a, ta = draw(f"la{M}.{K}", (M, K))
+    w, tw = draw(f"lw{V}.{K}", (V, K), 0.02)
+    tok = W.rng.zipf_tokens(3, f"t{M}.{V}", M, V)
+    tok[0], tok[-1] = V - 1, 0
+    out = torch.zeros(M, dtype=torch.float32, device=DEV)
+    B.specs_op_lmhead_logprob(ctx, ta, tw, torch.from_numpy(tok).to(DEV), out)
+    torch.cuda.synchronize()
+    want = oracle.token_logprob(a, w, tok)
+    assert np.abs(out.cpu().numpy() - want).max() < 2e-5 * max(1.0, np.abs(want).max())
+
+
+def test_lmhead_logprob_f32(ctx):
+    from paper_2506_15733_amd import binding as B
+    a, ta = draw("lfa", (37, 72), 1.0, "f32")
+    w, tw = draw("lfw", (515, 72), 0.3, "f32")
+    tok = W.rng.uniform_tokens(3, "lft", 37, 515)
+    out = torch.zeros(37, dtype=torch.float32, device=DEV)
+    B.specs_op_lmhead_logprob(ctx, ta, tw, torch.from_numpy(tok).to(DEV), out)
+    torch.cuda.synchronize()
+    assert np.abs(out.cpu().numpy() - oracle.token_logprob(a, w, tok)).max() < 5e-6
+
+
+def attention_case(ctx, desc, Bn, n, L, lens, page_tokens, sample_rows=None):
+    """Attention of layer 0 on random q/k/v and a random paged prefix, against oracle.attention row by row."""
+    from paper_2506_15733_amd import binding as B
+    tdt = torch.bfloat16 if desc.dtype == "bf16" else torch.float32
+    Hq, Hkv, hd = desc.n_q_heads, desc.n_kv_heads, desc.head_dim
+    M = Bn * n * L
+    need = [(l + page_tokens - 1) // page_tokens for l in lens]
+    perm = W.rng.permutation(5, "pg", sum(need))
+    table = np.full((Bn, max(need)), -1, np.int32)
+    o = 0
+    for b in range(Bn):
+        table[b, :need[b]] = perm[o:o + need[b]]
+        o += need[b]
+    num_pages = sum(need)
+    q, tq = draw("aq", (M, Hq, hd), 1.0, desc.dtype)
+    kb, tkb = draw("akb", (M, Hkv, hd), 1.0, desc.dtype)
+    vb, tvb = draw("avb", (M, Hkv, hd), 1.0, desc.dtype)
+    pool, tpool = draw("apool", (1, 2, num_pages, Hkv, page_tokens, hd), 1.0, desc.dtype)
+    cdesc = B.make_desc(1, desc.d_model, Hq, Hkv, hd, desc.ffn, desc.vocab, desc.dtype, "prm")
+    dummy = torch.zeros(max(desc.d_model, 64), dtype=tdt, device=DEV)
+    ones = torch.ones(desc.d_model, dtype=torch.float32, device=DEV)
+    layer = dict(wqkv=dummy, wo=dummy, wgu=dummy, wd=dummy, g_attn=ones, g_ffn=ones)
+    model = B.specs_model_create(ctx, cdesc, dummy, dummy, ones, [layer])
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    h_last = torch.zeros((Bn, desc.d_model), dtype=torch.float32, device=DEV)
+    ttable = torch.from_numpy(table).to(DEV)
+    prefix = B.specs_prefix_create(ctx, model, lens, lens_dev, page_tokens, tpool, num_pages, ttable, h_last)
+    out = torch.zeros((M, Hq * hd), dtype=tdt, device=DEV)
+    B.specs_op_attention(ctx, model, prefix, 0, tq, tkb, tvb, n, L, out)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    B.specs_prefix_destroy(prefix)
+    B.specs_model_destroy(model)
+    worst = 0.0
+    cands = [(b, i) for b in range(Bn) for i in range(n)]
+    if sample_rows is not None:
+        cands = [cands[j] for j in sample_rows]
+    for b, i in cands:
+        P = lens[b]
+        pk = np.stack([pool[0, 0, table[b, j // page_tokens], :, j % page_tokens, :] for j in range(P)])
+        pv = np.stack([pool[0, 1, table[b, j // page_tokens], :, j % page_tokens, :] for j in range(P)])
+        r0 = (b * n + i) * L
+        k = np.concatenate([pk, kb[r0:r0 + L]]).astype(np.float64)
+        v = np.concatenate([pv, vb[r0:r0 + L]]).astype(np.float64)
+        mask = np.concatenate([np.ones((L, P), bool), np.tril(np.ones((L, L), bool))], 1)
+        want = oracle.operand(oracle.attention(q[r0:r0 + L].astype(np.float64), k, v, mask, desc.dtype), desc.dtype)
+        worst = max(worst, np.abs(got[r0:r0 + L] - want).max())
+    return worst
+
+
+def test_attention_f32_ragged(ctx):
+    d = ModelDesc("target", 1, 96, 6, 2, 16, 160, 301, "f32", "lm")
+    assert attention_case(ctx, d, 3, 3, 5, [38, 8, 20], 4) < 2e-6
+
+
+@pytest.mark.parametrize("Hq,Hkv,hd,Bn,n,L,lens,pt", [
+    (6, 2, 16, 3, 3, 5, [38, 8, 20], 4),             # SIMT path: head_dim 16
+    (16, 8, 64, 1, 8, 32, [512], 16),                # config-2 shape
+    (12, 2, 128, 2, 3, 64, [333, 1000], 16),         # ragged prefix lengths, group of 6
+    (28, 4, 128, 1, 16, 128, [4096], 16),            # config-4 shape (sampled candidates)
+    (14, 2, 64, 1, 2, 70, [100], 16),                # block length not a multiple of any tile
+])
+def test_attention_bf16(ctx, Hq, Hkv, hd, Bn, n, L, lens, pt):
+    d = ModelDesc("target", 1, Hq * hd, Hq, Hkv, hd, 64, 64, "bf16", "lm")
+    sample = None if Bn * n <= 8 else [0, 7, Bn * n - 1]
+    err = attention_case(ctx, d, Bn, n, L, lens, pt, sample)
+    # outputs are O(1) averages of unit normals rounded to bf16: one bf16 ulp of the largest plausible value
+    assert err < 2.0 ** -7, err

@@ -1,0 +1,81 @@
+"""SubSample kernel against the sequential float64 oracle: indices must be bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workload as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2506_15733_amd import binding as B
+    ws = torch.zeros(4096, dtype=torch.uint8, device="cuda:0")
+    c = B.specs_ctx_create(0, torch.cuda.current_stream().cuda_stream, ws)
+    yield c
+    B.specs_ctx_destroy(c)
+
+
+def run(ctx, lt, ld, r, betas, u, mask=None):
+    from paper_2506_15733_amd import binding as B
+    dev = "cuda:0"
+    t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(dev)
+    idx = torch.full((lt.shape[0], len(betas)), -7, dtype=torch.int32, device=dev)
+    mr = torch.zeros(lt.shape[0], dtype=torch.float32, device=dev)
+    B.specs_subsample(ctx, t(lt, torch.float32), t(ld, torch.float32), t(r, torch.float32), betas, t(u, torch.float64),
+                      idx, None if mask is None else t(mask, torch.uint8), mr)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), mr.cpu().numpy(), B.specs_ctx_status(ctx)
+
+
+@pytest.mark.parametrize("n", [1, 4, 16, 64, 100, 1024])
+def test_indices_bit_exact_on_synthetic_scores(ctx, n):
+    wl = W.get_config("c5_7b_batched")
+    Bn = 64
+    lt, ld, r = wl.synthetic_scores(Bn, n)
+    betas = (0.0, 0.25, 1.0, 4.0, 16.0, 100.0, 1e4)
+    u = W.rng.uniform_f64(1, f"u{n}", Bn * len(betas)).reshape(Bn, -1)
+    idx, mr, st = run(ctx, lt, ld, r, betas, u)
+    want, want_mr = oracle.subsample_batch(lt, ld, r, betas, u)
+    assert st == 0
+    assert np.array_equal(idx, np.asarray(want))
+    assert np.array_equal(mr, np.asarray(want_mr, dtype=np.float32))
+    if n >= 16:
+        assert len(np.unique(idx[:, 1])) > 3          # low beta spreads the picks: the test is not vacuous
+
+
+def test_boundaries_masks_and_edge_uniforms(ctx):
+    lt = np.zeros((3, 4), np.float32); ld = np.zeros((3, 4), np.float32); r = np.zeros((3, 4), np.float32)
+    u = np.array([[0.0, 0.25], [0.5, 0.75 - 1e-12], [np.nextafter(1.0, 0), 0.2499999]])
+    idx, _, st = run(ctx, lt, ld, r, (1.0, 3.0), u)
+    assert st == 0 and idx.tolist() == [[0, 1], [2, 2], [3, 0]]
+    mask = np.array([[0, 0, 1, 1], [1, 0, 0, 0], [0, 1, 0, 1]], np.uint8)
+    idx, _, st = run(ctx, lt, ld, r, (1.0, 3.0), u, mask)
+    want, _ = oracle.subsample_batch(lt, ld, r, (1.0, 3.0), u, mask)
+    assert st == 0 and idx.tolist() == want
+
+
+def test_overflow_safe_at_tuned_beta(ctx):
+    lt = np.array([[-1000.0, 0.0, -10.0]], np.float32); ld = np.array([[0.0, -1000.0, -10.0]], np.float32)
+    r = np.array([[0.2, 0.1, 0.9]], np.float32)
+    idx, _, st = run(ctx, lt, ld, r, (1e2, 1e4), np.array([[0.7, 0.7]]))
+    assert st == 0 and idx.tolist() == [[1, 2]]
+
+
+def test_device_side_errors_are_reported_not_fatal(ctx):
+    from paper_2506_15733_amd import binding as B
+    z = np.zeros((1, 4), np.float32)
+    idx, _, st = run(ctx, z, z, z, (1.0,), np.array([[1.0]]))
+    assert st == 4 and idx.tolist() == [[-1]]                                  # u outside [0,1)
+    bad = z.copy(); bad[0, 2] = np.nan
+    idx, _, st = run(ctx, bad, z, z, (1.0,), np.array([[0.3]]))
+    assert st == 5 and idx.tolist() == [[-1]]                                  # NaN score
+    idx, _, st = run(ctx, z, z, z, (1.0,), np.array([[0.3]]), np.zeros((1, 4), np.uint8))
+    assert st == 5 and idx.tolist() == [[-1]]                                  # nobody live
+    with pytest.raises(B.SpecsError) as e:
+        run(ctx, z, z, z, (-1.0,), np.array([[0.3]]))
+    assert e.value.code == 4
+    idx, _, st = run(ctx, z, z, z, (1.0,), np.array([[0.3]]))
+    assert st == 0 and idx.tolist() == [[1]]                                   # the context is still usable

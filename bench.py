@@ -65,14 +65,79 @@ def cpu_baseline(wl, budget_layers=2, n_sub=2):
                       f"float64 numpy; scaled linearly to all layers, candidates and beams"}
 
 
+def kernel_bench(args):
+    """Loop one contraction kernel of the pass at the workload's target-model shape (for profiling and tuning)."""
+    import torch
+    import workload as W
+    from workload.configs import device_tensor
+    from paper_2506_15733_amd import binding as B, synthetic
+    wl = W.get_config(args.workload)
+    d = wl.target
+    dev = "cuda:0"
+    M = wl.B * wl.n * wl.L
+    qd, kvd = d.n_q_heads * d.head_dim, d.n_kv_heads * d.head_dim
+    ws = torch.zeros(2 << 30, dtype=torch.uint8, device=dev)
+    ctx = B.specs_ctx_create(0, torch.cuda.current_stream().cuda_stream, ws)
+    bf = lambda *s: (torch.randn(s, device=dev) * 0.5).to(torch.bfloat16)
+    wt = lambda n, k: device_tensor(d, 0, f"bench/{n}.{k}", (n, k), dev)
+    k = args.kernel
+    if k == "gate_up":
+        A, Wm, out = bf(M, d.d_model), wt(2 * d.ffn, d.d_model), torch.empty((M, d.ffn), dtype=torch.bfloat16, device=dev)
+        fn, flops = (lambda: B.specs_op_gate_up(ctx, A, Wm, out)), 2.0 * M * d.d_model * 2 * d.ffn
+    elif k in ("qkv", "o", "down"):
+        N, K = {"qkv": (qd + 2 * kvd, d.d_model), "o": (d.d_model, qd), "down": (d.d_model, d.ffn)}[k]
+        A, Wm, out = bf(M, K), wt(N, K), torch.zeros((M, N), dtype=torch.float32, device=dev)
+        fn, flops = (lambda: B.specs_op_linear(ctx, A, Wm, out, accumulate=(k != "qkv"))), 2.0 * M * N * K
+    elif k == "lmhead":
+        A, Wm = bf(M, d.d_model), wt(d.vocab, d.d_model)
+        tok = torch.randint(0, d.vocab, (M,), dtype=torch.int32, device=dev)
+        out = torch.empty(M, dtype=torch.float32, device=dev)
+        fn, flops = (lambda: B.specs_op_lmhead_logprob(ctx, A, Wm, tok, out)), 2.0 * M * d.d_model * d.vocab
+    elif k == "attn":
+        step_prefix_len = wl.prefix_lens()
+        table, num_pages = wl.page_table()
+        cdesc = B.make_desc(1, d.d_model, d.n_q_heads, d.n_kv_heads, d.head_dim, d.ffn, d.vocab, d.dtype, "prm")
+        dummy = torch.zeros(max(d.d_model, 64), dtype=torch.bfloat16, device=dev)
+        ones = torch.ones(d.d_model, dtype=torch.float32, device=dev)
+        model = B.specs_model_create(ctx, cdesc, dummy, dummy, ones,
+                                     [dict(wqkv=dummy, wo=dummy, wgu=dummy, wd=dummy, g_attn=ones, g_ffn=ones)])
+        pool = bf(1, 2, num_pages, d.n_kv_heads, wl.page_tokens * d.head_dim)
+        lens = [int(x) for x in step_prefix_len]
+        lens_dev = torch.tensor(lens, dtype=torch.int32, device=dev)
+        h_last = torch.zeros((wl.B, d.d_model), dtype=torch.float32, device=dev)
+        ttab = torch.from_numpy(table).to(dev)
+        prefix = B.specs_prefix_create(ctx, model, lens, lens_dev, wl.page_tokens, pool, num_pages, ttab, h_last)
+        q, kb, vb = bf(M, qd), bf(M, kvd), bf(M, kvd)
+        out = torch.empty((M, qd), dtype=torch.bfloat16, device=dev)
+        fn = lambda: B.specs_op_attention(ctx, model, prefix, 0, q, kb, vb, wl.n, wl.L, out)
+        flops = 4.0 * qd * (sum(l * wl.n * wl.L for l in lens) + wl.B * wl.n * wl.L * (wl.L + 1) / 2.0)
+    else:
+        raise SystemExit(f"unknown kernel {k}")
+    for _ in range(3):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.reps
+    print(json.dumps({"kernel": k, "workload": wl.name, "ms": ms, "tflops": flops / ms / 1e9,
+                      "frac_mfma_peak": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}))
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--kernel", default=None, help="gate_up|qkv|o|down|lmhead|attn: time that kernel alone")
+    ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c4_7b")
     ap.add_argument("--no-cpu", action="store_true")
     args = ap.parse_args()
+    if args.kernel:
+        return kernel_bench(args)
     if args.gpus != 1:
         print("bench.py measures the one-GPU share of the path; --gpus must be 1 (nothing here uses a second GPU)",
               file=sys.stderr)

@@ -89,8 +89,8 @@ typedef struct specs_weights {
 } specs_weights;
 
 /* Bytes of workspace that calls with at most max_rows = B*n*L block tokens (or prefill chunk
- * rows) over at most max_B prefixes need for this model. Pure host arithmetic. */
-size_t specs_workspace_bytes(const specs_model_desc* desc, int64_t max_rows, int32_t max_B);
+ * rows) in at most max_blocks = B*n candidate blocks need for this model. Pure host arithmetic. */
+size_t specs_workspace_bytes(const specs_model_desc* desc, int64_t max_rows, int32_t max_blocks);
 
 /* Context: device ordinal, a hipStream_t (NULL = the default stream) and the caller's workspace
  * (256-byte aligned). The context keeps no other device memory. */
@@ -105,8 +105,10 @@ int specs_model_create(specs_ctx* ctx, const specs_model_desc* desc, const specs
 int specs_model_destroy(specs_model* m);
 
 /* The cached trace tr of B independent beams for one model: a paged key/value pool
- *   kv_pool[n_layers][2 (K,V)][num_pages][Hkv][page_tokens][head_dim]   (element type = model dtype;
- *   keys are stored after the rotary embedding),
+ *   kv_pool[n_layers][2][num_pages][Hkv][page_tokens * head_dim]   (element type = model dtype), where a
+ *   key page-head is [page_tokens][head_dim] (keys stored after the rotary embedding) and a value
+ *   page-head is stored transposed, [head_dim][page_tokens], which is the operand order of the
+ *   second attention product; the pool must be initialised (no NaN/Inf bit patterns in unused slots),
  * a page table page_table[B][max_pages] of physical page numbers (token j of beam b lives in page
  * page_table[b][j / page_tokens], slot j % page_tokens), the lengths lens[B] (given on host AND on
  * device) and h_last[B][d]: the float residual-stream output of the last layer at the last prefix

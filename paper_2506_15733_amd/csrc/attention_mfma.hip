@@ -1,0 +1,293 @@
+// Shared-prefix paged attention on MFMA (bf16, head_dim 64 or 128, 16-token pages).
+//
+// Work decomposition. For one beam b, candidate i and kv head, the g = Hq/Hkv query heads of the
+// L block tokens are stacked into L*g rows (row r = t*g + j: token t, query head kvh*g + j) that
+// all read the same keys. A workgroup (4 wavefronts) owns 32*QT*4 of those rows and walks over
+// the keys in tiles of 64: first the beam's cached prefix (4 pages per tile), then the
+// candidate's own block (causal). The n candidates of a beam run as neighbouring workgroups on the
+// same XCD, so the prefix pages are fetched from HBM once and re-read from L2.
+//
+// Per tile (flash-attention recurrence, float state):
+//   S^T[key, q] = K Q^T   (MFMA 32x32x16, A = keys from LDS, B = queries held in registers)
+//   m' = max(m, max_key S), alpha = exp(m - m'), p = exp(S - m'), l = l*alpha + sum p
+//   O^T[d, q] = O^T*alpha + V^T P^T   (A = V^T from LDS, B = p rounded to bf16)
+// In the transposed orientation a lane owns one query column, so the max over keys is a reduction
+// over the lane's own 32 accumulator values plus one exchange with the other half-wave, and the
+// rescale by alpha is a per-lane scalar.
+//
+// The A-rows of the S^T product are fed with keys in the order pi(i) (the two middle groups of
+// four swapped inside every 16) so that the eight accumulator values a lane holds for one MFMA
+// K-step of the second product are eight CONSECUTIVE keys: with V stored transposed
+// ([head_dim][16 tokens] per page) the matching A-operand is one 16-byte LDS read.
+#include "common.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+struct AttnArgs {
+  const bf16_t* q;      // [M][Hq][hd]
+  const bf16_t* kb;     // [M][Hkv][hd] block keys
+  const bf16_t* vbT;    // [B*n][Hkv][hd][Lp] block values, transposed, zero padded
+  const bf16_t* poolK;  // [pages][Hkv][16][hd]
+  const bf16_t* poolV;  // [pages][Hkv][hd][16]
+  bf16_t* out;          // [M][Hq*hd]
+  BatchGeom g;
+  int Hq, Hkv, Lp, q_tiles, total_wg, wg_per_xcd;
+  float scale_log2e;
+};
+
+template <int HD>
+__device__ __forceinline__ int k_swizzle(int row, int chunk) {
+  return HD == 128 ? (chunk ^ (row & 15)) : (chunk ^ ((row >> 1) & 7));
+}
+
+template <int HD, int QT>
+__global__ void __launch_bounds__(256) attention_mfma_kernel(AttnArgs a) {
+  constexpr int KROW = HD * 2;              // bytes per key row
+  constexpr int KCH = HD / 8;               // 16-byte chunks per key row
+  constexpr int K_BYTES = 64 * KROW;        // 64 keys
+  constexpr int V_BYTES = 4 * HD * 32;      // 4 pages of [HD][16]
+  constexpr int STAGE = K_BYTES + V_BYTES;
+  constexpr int NI = HD / 32;               // direct-to-LDS instructions per wave per operand; also d-tiles
+  constexpr int KS = HD / 16;               // MFMA K-steps of the S^T product
+  constexpr int BQ = 128 * QT;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+  // workgroup id -> logical index: each XCD (id % 8) takes a contiguous run of the (beam, kv head, candidate, tile) list
+  const int logical = (blockIdx.x & 7) * a.wg_per_xcd + (blockIdx.x >> 3);
+  if (logical >= a.total_wg) return;
+  const BatchGeom& G = a.g;
+  const int g = a.Hq / a.Hkv;
+  int rem = logical;
+  const int qt_idx = rem % a.q_tiles; rem /= a.q_tiles;
+  const int cand = rem % G.n; rem /= G.n;
+  const int kvh = rem % a.Hkv;
+  const int b = rem / a.Hkv;
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int lq = lane & 31, lh = lane >> 5;
+  const int P = G.len_override >= 0 ? G.len_override : G.lens[G.b0 + b];
+  const int L = G.L;
+  const int cand_idx = b * G.n + cand;
+  const size_t m_c0 = (size_t)cand_idx * L;                 // first row of this candidate
+  const int rows_total = L * g;
+  const int r_wg0 = qt_idx * BQ;
+  const int32_t* ptab = G.page_table + (size_t)(G.b0 + b) * G.max_pages;
+
+  // --- queries of this wavefront as B-operand fragments (column = query) ---
+  int tq[QT];
+  bf16x8 qf[QT][KS];
+#pragma unroll
+  for (int u = 0; u < QT; ++u) {
+    int r = r_wg0 + (wave * QT + u) * 32 + lq;
+    int rc = r < rows_total ? r : rows_total - 1;
+    int t = rc / g, j = rc - t * g;
+    tq[u] = t;
+    const bf16_t* src = a.q + ((m_c0 + t) * a.Hq + (size_t)kvh * g + j) * HD;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[u][ks] = *(const bf16x8*)(src + ks * 16 + lh * 8);
+  }
+
+  floatx16 o[QT][NI];
+  float m_run[QT], l_run[QT];
+#pragma unroll
+  for (int u = 0; u < QT; ++u) {
+    m_run[u] = -INFINITY;
+    l_run[u] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < NI; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[u][dt][r] = 0.f;
+  }
+
+  const int n_ptiles = (P + 63) >> 6;
+  const int n_pages = (P + 15) >> 4;
+  int t_hi = (r_wg0 + BQ - 1) / g;
+  t_hi = t_hi < L - 1 ? t_hi : L - 1;
+  const int n_btiles = (r_wg0 < rows_total) ? (t_hi >> 6) + 1 : 0;
+  const int n_tiles = n_ptiles + n_btiles;
+
+  // one wavefront stages one 16-key group (a page, or 16 block tokens) of the tile: K rows and V^T
+  auto stage_tile = [&](int tile, char* buf) {
+    char* kdst = buf + wave * 16 * KROW;
+    char* vdst = buf + K_BYTES + wave * HD * 32;
+    if (tile < n_ptiles) {
+      int pg = tile * 4 + wave;
+      pg = pg < n_pages ? pg : n_pages - 1;
+      size_t page = (size_t)ptab[pg];
+      const bf16_t* ksrc = a.poolK + (page * a.Hkv + kvh) * 16 * HD;
+      const bf16_t* vsrc = a.poolV + (page * a.Hkv + kvh) * HD * 16;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        int qi = i * 64 + lane;
+        int row = qi / KCH, slot = qi % KCH;
+        int chunk = k_swizzle<HD>(wave * 16 + row, slot);
+        __builtin_amdgcn_global_load_lds(GLB_PTR(ksrc + row * HD + chunk * 8), LDS_PTR(kdst + i * 1024), 16, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+        __builtin_amdgcn_global_load_lds(GLB_PTR(vsrc + (i * 64 + lane) * 8), LDS_PTR(vdst + i * 1024), 16, 0, 0);
+    } else {
+      int key0 = (tile - n_ptiles) * 64 + wave * 16;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        int qi = i * 64 + lane;
+        int row = qi / KCH, slot = qi % KCH;
+        int chunk = k_swizzle<HD>(wave * 16 + row, slot);
+        int key = key0 + row;
+        key = key < L ? key : L - 1;
+        const bf16_t* src = a.kb + ((m_c0 + key) * a.Hkv + kvh) * HD + chunk * 8;
+        __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(kdst + i * 1024), 16, 0, 0);
+      }
+      const bf16_t* vsrc = a.vbT + ((size_t)cand_idx * a.Hkv + kvh) * HD * a.Lp;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        int qi = i * 64 + lane;
+        int d = qi >> 1, half = qi & 1;
+        int key = key0 + half * 8;
+        key = key < a.Lp ? key : a.Lp - 8;
+        __builtin_amdgcn_global_load_lds(GLB_PTR(vsrc + (size_t)d * a.Lp + key), LDS_PTR(vdst + i * 1024), 16, 0, 0);
+      }
+    }
+  };
+
+  if (n_tiles > 0) stage_tile(0, smem);
+  // pi(i): A-row i of the S^T product carries key pi(i) of the 32-key half tile
+  const int pi_row = (lq & 16) | ((lq & 4) << 1) | ((lq & 8) >> 1) | (lq & 3);
+
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tile + 1 < n_tiles) stage_tile(tile + 1, smem + ((tile + 1) & 1) * STAGE);
+    const char* Ks = smem + (tile & 1) * STAGE;
+    const char* Vs = Ks + K_BYTES;
+    const bool is_block = tile >= n_ptiles;
+    const int key_base = is_block ? (tile - n_ptiles) * 64 : tile * 64;
+
+    // S^T for the two 32-key halves
+    floatx16 s[QT][2];
+#pragma unroll
+    for (int u = 0; u < QT; ++u)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[u][hf][r] = 0.f;
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      int row = hf * 32 + pi_row;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 kf = *(const bf16x8*)(Ks + row * KROW + (k_swizzle<HD>(row, ks * 2 + lh) << 4));
+#pragma unroll
+        for (int u = 0; u < QT; ++u) s[u][hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[u][ks], s[u][hf], 0, 0, 0);
+      }
+    }
+
+    // accumulator value r of half hf in this lane is key  key_base + hf*32 + 16*(r/8) + 8*lh + r%8
+    bf16x8 pf[QT][4];
+#pragma unroll
+    for (int u = 0; u < QT; ++u) {
+      const bool need_mask = is_block || (key_base + 64 > P);
+      const int limit = is_block ? tq[u] + 1 : P;      // keys < limit are visible
+      float mx = -INFINITY;
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = s[u][hf][r] * a.scale_log2e;
+          if (need_mask) {
+            int key = key_base + hf * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
+            v = key < limit ? v : -INFINITY;
+          }
+          s[u][hf][r] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      float m_new = fmaxf(m_run[u], mx);
+      float alpha, m_use;
+      if (m_new == -INFINITY) { alpha = 1.f; m_use = 0.f; }   // nothing visible yet: p = exp2(-inf) = 0
+      else { alpha = exp2f(m_run[u] - m_new); m_use = m_new; }
+      m_run[u] = m_new;
+      float psum = 0.f;
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float p = exp2f(s[u][hf][r] - m_use);
+          psum += p;
+          pf[u][hf * 2 + (r >> 3)][r & 7] = (bf16_t)p;
+        }
+      l_run[u] = l_run[u] * alpha + psum;
+#pragma unroll
+      for (int dt = 0; dt < NI; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[u][dt][r] *= alpha;
+    }
+
+    // O^T += V^T P^T : K-step = one 16-key group (page) pg, this lane supplies keys 8*lh .. 8*lh+7 of it
+#pragma unroll
+    for (int pg = 0; pg < 4; ++pg)
+#pragma unroll
+      for (int dt = 0; dt < NI; ++dt) {
+        bf16x8 vf = *(const bf16x8*)(Vs + pg * HD * 32 + (dt * 32 + lq) * 32 + lh * 16);
+#pragma unroll
+        for (int u = 0; u < QT; ++u) o[u][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u][pg], o[u][dt], 0, 0, 0);
+      }
+  }
+
+  // normalise and store: lane = query column, accumulator value r of d-tile dt is d = dt*32 + 8*(r/4) + 4*lh + r%4
+#pragma unroll
+  for (int u = 0; u < QT; ++u) {
+    int r = r_wg0 + (wave * QT + u) * 32 + lq;
+    float l = l_run[u] + __shfl_xor(l_run[u], 32, 64);
+    if (r < rows_total) {
+      int t = r / g, j = r - t * g;
+      float inv = 1.0f / l;
+      bf16_t* dst = a.out + ((m_c0 + t) * a.Hq + (size_t)kvh * g + j) * HD;
+#pragma unroll
+      for (int dt = 0; dt < NI; ++dt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          int d = dt * 32 + 8 * r4 + 4 * lh;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) dst[d + e] = (bf16_t)(o[u][dt][r4 * 4 + e] * inv);
+        }
+    }
+  }
+}
+
+template <int HD, int QT>
+static void launch_attn_variant(const AttnArgs& a, hipStream_t s) {
+  constexpr int smem = 2 * (64 * HD * 2 + 4 * HD * 32);
+  static bool configured = false;
+  if (!configured) {
+    (void)hipFuncSetAttribute((const void*)attention_mfma_kernel<HD, QT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              smem);
+    configured = true;
+  }
+  attention_mfma_kernel<HD, QT><<<dim3(a.wg_per_xcd * 8), 256, smem, s>>>(a);
+}
+
+// Returns false if the shape is not one this kernel takes (head_dim 64/128, 16-token pages).
+bool launch_attention_mfma(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT, const bf16_t* poolK,
+                           const bf16_t* poolV, bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp,
+                           hipStream_t s) {
+  if ((md.hd != 64 && md.hd != 128) || g.page_tokens != 16 || Lp % 16 != 0) return false;
+  AttnArgs a;
+  a.q = q; a.kb = kb; a.vbT = vbT; a.poolK = poolK; a.poolV = poolV; a.out = out; a.g = g;
+  a.Hq = md.Hq; a.Hkv = md.Hkv; a.Lp = Lp;
+  a.scale_log2e = 1.4426950408889634f / sqrtf((float)md.hd);
+  int rows = g.L * (md.Hq / md.Hkv);
+  // 256-row workgroups when they waste no more padding than 128-row ones
+  int t1 = (rows + 127) / 128, t2 = (rows + 255) / 256;
+  bool big = t2 * 256 <= t1 * 128;
+  a.q_tiles = big ? t2 : t1;
+  a.total_wg = g.B * md.Hkv * g.n * a.q_tiles;
+  a.wg_per_xcd = (a.total_wg + 7) / 8;
+  if (md.hd == 128) { if (big) launch_attn_variant<128, 2>(a, s); else launch_attn_variant<128, 1>(a, s); }
+  else { if (big) launch_attn_variant<64, 2>(a, s); else launch_attn_variant<64, 1>(a, s); }
+  return true;
+}

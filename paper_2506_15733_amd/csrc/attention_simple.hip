@@ -5,9 +5,9 @@
 
 template <typename T>
 __global__ void __launch_bounds__(64) attention_simple_kernel(const T* __restrict__ q, const T* __restrict__ kb,
-                                                              const T* __restrict__ vb, const T* __restrict__ poolK,
+                                                              const T* __restrict__ vbT, const T* __restrict__ poolK,
                                                               const T* __restrict__ poolV, T* __restrict__ out,
-                                                              BatchGeom g, int Hq, int Hkv, int hd, float scale) {
+                                                              BatchGeom g, int Hq, int Hkv, int hd, int Lp, float scale) {
   extern __shared__ float sc[];                 // [ctx + t + 1] scores, then weights
   int m = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
   int nL = g.n * g.L;
@@ -46,33 +46,36 @@ __global__ void __launch_bounds__(64) attention_simple_kernel(const T* __restric
   sm = wave_sum(sm);
   __syncthreads();
   float inv = 1.0f / sm;
+  // values are stored transposed: pages [page][Hkv][hd][pt], block [cand][Hkv][hd][Lp]
+  size_t cand = (size_t)(m / g.L);
   for (int c = lane; c < hd; c += 64) {
     float acc = 0.f;
+    const T* vblk = vbT + ((cand * Hkv + kvh) * hd + c) * Lp;
     for (int j = 0; j < nkeys; ++j) {
-      const T* vr;
+      float vv;
       if (j < ctx) {
         int page = pt[j / g.page_tokens], slot = j % g.page_tokens;
-        vr = poolV + (((size_t)page * Hkv + kvh) * g.page_tokens + slot) * hd;
+        vv = to_f32<T>(poolV[(((size_t)page * Hkv + kvh) * hd + c) * g.page_tokens + slot]);
       } else {
-        vr = vb + ((size_t)(m - t + (j - ctx)) * Hkv + kvh) * hd;
+        vv = to_f32<T>(vblk[j - ctx]);
       }
-      acc = fmaf(sc[j], to_f32<T>(vr[c]), acc);
+      acc = fmaf(sc[j], vv, acc);
     }
     out[((size_t)m * Hq + h) * hd + c] = from_f32<T>(acc * inv);
   }
 }
 
 template <typename T>
-void launch_attention_simple(const T* q, const T* kb, const T* vb, const T* poolK, const T* poolV, T* out,
-                             const BatchGeom& g, const ModelDims& md, int max_ctx, hipStream_t s) {
+void launch_attention_simple(const T* q, const T* kb, const T* vbT, const T* poolK, const T* poolV, T* out,
+                             const BatchGeom& g, const ModelDims& md, int Lp, int max_ctx, hipStream_t s) {
   size_t lds = (size_t)(max_ctx + g.L + md.hd) * sizeof(float);
   float scale = 1.0f / sqrtf((float)md.hd);
   (void)hipFuncSetAttribute((const void*)attention_simple_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  attention_simple_kernel<T><<<dim3(g.M, md.Hq), 64, lds, s>>>(q, kb, vb, poolK, poolV, out, g, md.Hq, md.Hkv, md.hd,
-                                                               scale);
+  attention_simple_kernel<T><<<dim3(g.M, md.Hq), 64, lds, s>>>(q, kb, vbT, poolK, poolV, out, g, md.Hq, md.Hkv, md.hd,
+                                                               Lp, scale);
 }
 template void launch_attention_simple<float>(const float*, const float*, const float*, const float*, const float*,
-                                             float*, const BatchGeom&, const ModelDims&, int, hipStream_t);
+                                             float*, const BatchGeom&, const ModelDims&, int, int, hipStream_t);
 template void launch_attention_simple<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, const bf16_t*,
-                                              const bf16_t*, bf16_t*, const BatchGeom&, const ModelDims&, int,
+                                              const bf16_t*, bf16_t*, const BatchGeom&, const ModelDims&, int, int,
                                               hipStream_t);

@@ -53,13 +53,17 @@ template <typename T>
 void launch_rmsnorm_shifted(const float* x, const float* h_last, const float* gain, T* out, const BatchGeom& g,
                             int d, float eps, hipStream_t s);
 void launch_rope_table(float* cs, const BatchGeom& g, int hd, float base, hipStream_t s);
+// values leave this kernel transposed per candidate: vT[cand][Hkv][hd][Lp], Lp = L rounded up to 16
 template <typename T>
-void launch_rope_split(const float* qkv, const float* cs, T* q, T* k, T* v, int M, const ModelDims& md, hipStream_t s);
+void launch_rope_split(const float* qkv, const float* cs, T* q, T* k, T* vT, const BatchGeom& g, int Lp,
+                       const ModelDims& md, hipStream_t s);
+template <typename T>
+void launch_transpose_v(const T* v, T* vT, int cands, int Hkv, int hd, int L, int Lp, hipStream_t s);
 template <typename T>
 void launch_silu_mul(const float* gu, T* act, int M, int F, hipStream_t s);
 template <typename T>
-void launch_kv_commit(const T* kb, const T* vb, T* poolK, T* poolV, const BatchGeom& g, const ModelDims& md,
-                      int cand_stride_rows, const int32_t* chosen, hipStream_t s);
+void launch_kv_commit(const T* kb, const T* vbT, T* poolK, T* poolV, const BatchGeom& g, const ModelDims& md,
+                      int Lp, const int32_t* chosen, hipStream_t s);
 template <typename T>
 void launch_prm_head(const float* x, const float* gain, const T* w, float* out, const BatchGeom& g, int d, float eps,
                      hipStream_t s);
@@ -71,8 +75,11 @@ template <typename T>
 void launch_gemm_simple(const T* A, const T* W, float* C, int M, int N, int K, GemmEpilogue epi, hipStream_t s);
 
 template <typename T>
-void launch_attention_simple(const T* q, const T* kb, const T* vb, const T* poolK, const T* poolV, T* out,
-                             const BatchGeom& g, const ModelDims& md, int max_ctx, hipStream_t s);
+void launch_attention_simple(const T* q, const T* kb, const T* vbT, const T* poolK, const T* poolV, T* out,
+                             const BatchGeom& g, const ModelDims& md, int Lp, int max_ctx, hipStream_t s);
+bool launch_attention_mfma(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT, const bf16_t* poolK,
+                           const bf16_t* poolV, bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp,
+                           hipStream_t s);
 
 // Fused vocabulary head: per (row, 64-column tile) partial (max, sum exp) and the target-token logit.
 template <typename T>
@@ -80,7 +87,7 @@ void launch_lmhead_partials_simple(const T* A, const T* W, const int32_t* tok, f
                                    float* zt, int M, int V, int K, int* n_tiles_out, hipStream_t s);
 int lmhead_simple_tiles(int V);
 void launch_lmhead_merge(const float* part_max, const float* part_sum, const float* zt, int n_tiles, float* tok_logp,
-                         float* block_out, const BatchGeom& g, hipStream_t s);
+                         float* tok_scratch, float* block_out, const BatchGeom& g, hipStream_t s);
 
 void launch_subsample(const float* lt, const float* lg, const float* r, const uint8_t* mask, int B, int n,
                       const float* beta_dev, int nb, const double* u, int32_t* idx, float* max_reward, int* status,

@@ -106,14 +106,17 @@ void launch_rope_table(float* cs, const BatchGeom& g, int hd, float base, hipStr
                                                         g.len_override);
 }
 
-// qkv float [M, Hq+2Hkv, hd] -> q T [M,Hq,hd] (rotated), k T [M,Hkv,hd] (rotated), v T [M,Hkv,hd]
+// qkv float [M, Hq+2Hkv, hd] -> q T [M,Hq,hd] (rotated), k T [M,Hkv,hd] (rotated),
+// v T transposed per candidate: vT[cand][Hkv][hd][Lp] (Lp = L rounded up to 16, padding zeroed).
 template <typename T>
 __global__ void rope_split_kernel(const float* __restrict__ qkv, const float* __restrict__ cs, T* __restrict__ q,
-                                  T* __restrict__ k, T* __restrict__ v, int Hq, int Hkv, int hd) {
+                                  T* __restrict__ k, T* __restrict__ vT, int Hq, int Hkv, int hd, int L, int Lp) {
   size_t m = blockIdx.x;
   int H = Hq + 2 * Hkv, half = hd / 2;
   const float* in = qkv + m * (size_t)H * hd;
   const float* c = cs + m * hd;
+  size_t cand = m / L;
+  int t = (int)(m % L);
   for (int e = threadIdx.x; e < H * half; e += blockDim.x) {
     int h = e / half, i = e % half;
     float x1 = in[h * hd + i], x2 = in[h * hd + half + i];
@@ -124,20 +127,43 @@ __global__ void rope_split_kernel(const float* __restrict__ qkv, const float* __
       o[i] = from_f32<T>(y1);
       o[half + i] = from_f32<T>(y2);
     } else {
-      T* o = v + (m * Hkv + (h - Hq - Hkv)) * hd;
-      o[i] = from_f32<T>(x1);
-      o[half + i] = from_f32<T>(x2);
+      T* o = vT + ((cand * Hkv + (h - Hq - Hkv)) * hd) * Lp + t;
+      o[(size_t)i * Lp] = from_f32<T>(x1);
+      o[(size_t)(half + i) * Lp] = from_f32<T>(x2);
     }
+  }
+  if (t == L - 1 && Lp > L) {
+    for (int e = threadIdx.x; e < Hkv * hd; e += blockDim.x)
+      for (int tt = L; tt < Lp; ++tt) vT[(cand * Hkv * hd + e) * Lp + tt] = from_f32<T>(0.f);
   }
 }
 template <typename T>
-void launch_rope_split(const float* qkv, const float* cs, T* q, T* k, T* v, int M, const ModelDims& md, hipStream_t s) {
-  rope_split_kernel<T><<<M, 256, 0, s>>>(qkv, cs, q, k, v, md.Hq, md.Hkv, md.hd);
+void launch_rope_split(const float* qkv, const float* cs, T* q, T* k, T* vT, const BatchGeom& g, int Lp,
+                       const ModelDims& md, hipStream_t s) {
+  rope_split_kernel<T><<<g.M, 256, 0, s>>>(qkv, cs, q, k, vT, md.Hq, md.Hkv, md.hd, g.L, Lp);
 }
-template void launch_rope_split<float>(const float*, const float*, float*, float*, float*, int, const ModelDims&,
-                                       hipStream_t);
-template void launch_rope_split<bf16_t>(const float*, const float*, bf16_t*, bf16_t*, bf16_t*, int, const ModelDims&,
-                                        hipStream_t);
+template void launch_rope_split<float>(const float*, const float*, float*, float*, float*, const BatchGeom&, int,
+                                       const ModelDims&, hipStream_t);
+template void launch_rope_split<bf16_t>(const float*, const float*, bf16_t*, bf16_t*, bf16_t*, const BatchGeom&, int,
+                                        const ModelDims&, hipStream_t);
+
+// v [M][Hkv][hd] -> vT [cand][Hkv][hd][Lp], zero padded (used when values arrive in token-major order)
+template <typename T>
+__global__ void transpose_v_kernel(const T* __restrict__ v, T* __restrict__ vT, int Hkv, int hd, int L, int Lp) {
+  size_t cand = blockIdx.x;
+  size_t per = (size_t)Hkv * hd;
+  for (size_t e = threadIdx.x; e < per * Lp; e += blockDim.x) {
+    size_t hc = e / Lp;
+    int t = (int)(e % Lp);
+    vT[cand * per * Lp + e] = t < L ? v[(cand * L + t) * per + hc] : from_f32<T>(0.f);
+  }
+}
+template <typename T>
+void launch_transpose_v(const T* v, T* vT, int cands, int Hkv, int hd, int L, int Lp, hipStream_t s) {
+  transpose_v_kernel<T><<<cands, 256, 0, s>>>(v, vT, Hkv, hd, L, Lp);
+}
+template void launch_transpose_v<float>(const float*, float*, int, int, int, int, int, hipStream_t);
+template void launch_transpose_v<bf16_t>(const bf16_t*, bf16_t*, int, int, int, int, int, hipStream_t);
 
 // ---------------------------------------------------------------- SiLU(gate) * up
 // gu float [M, 2F] in the interleaved-by-32 column order of the fused gate/up matrix.
@@ -160,29 +186,31 @@ template void launch_silu_mul<float>(const float*, float*, int, int, hipStream_t
 template void launch_silu_mul<bf16_t>(const float*, bf16_t*, int, int, hipStream_t);
 
 // ---------------------------------------------------------------- KV commit into pages
-// Copies L block rows of one candidate per beam (chosen[b], or candidate 0 when chosen == NULL)
-// to positions ctx .. ctx+L-1 of the beam's pages. grid = (L, B), one block per token.
+// Copies the L block tokens of one candidate per beam (chosen[b], or candidate 0 when chosen == NULL)
+// to positions ctx .. ctx+L-1 of the beam's pages: keys [page][Hkv][pt][hd], values transposed
+// [page][Hkv][hd][pt]. grid = (L, B), one block per token.
 template <typename T>
-__global__ void kv_commit_kernel(const T* __restrict__ kb, const T* __restrict__ vb, T* __restrict__ poolK,
-                                 T* __restrict__ poolV, BatchGeom g, int Hkv, int hd, const int32_t* __restrict__ chosen) {
+__global__ void kv_commit_kernel(const T* __restrict__ kb, const T* __restrict__ vbT, T* __restrict__ poolK,
+                                 T* __restrict__ poolV, BatchGeom g, int Hkv, int hd, int Lp,
+                                 const int32_t* __restrict__ chosen) {
   int t = blockIdx.x, b = blockIdx.y;
   int i = chosen ? chosen[b] : 0;
   int ctx = g.len_override >= 0 ? g.len_override : g.lens[g.b0 + b];
   int pos = ctx + t;
   int page = g.page_table[(size_t)(g.b0 + b) * g.max_pages + pos / g.page_tokens];
   int slot = pos % g.page_tokens;
-  size_t m = ((size_t)b * g.n + i) * g.L + t;
+  size_t cand = (size_t)b * g.n + i;
+  size_t m = cand * g.L + t;
   for (int e = threadIdx.x; e < Hkv * hd; e += blockDim.x) {
     int h = e / hd, c = e % hd;
-    size_t dst = (((size_t)page * Hkv + h) * g.page_tokens + slot) * hd + c;
-    poolK[dst] = kb[m * Hkv * hd + e];
-    poolV[dst] = vb[m * Hkv * hd + e];
+    poolK[(((size_t)page * Hkv + h) * g.page_tokens + slot) * hd + c] = kb[m * Hkv * hd + e];
+    poolV[(((size_t)page * Hkv + h) * hd + c) * g.page_tokens + slot] = vbT[(cand * Hkv * hd + e) * Lp + t];
   }
 }
 template <typename T>
-void launch_kv_commit(const T* kb, const T* vb, T* poolK, T* poolV, const BatchGeom& g, const ModelDims& md,
-                      int /*unused*/, const int32_t* chosen, hipStream_t s) {
-  kv_commit_kernel<T><<<dim3(g.L, g.B), 256, 0, s>>>(kb, vb, poolK, poolV, g, md.Hkv, md.hd, chosen);
+void launch_kv_commit(const T* kb, const T* vbT, T* poolK, T* poolV, const BatchGeom& g, const ModelDims& md, int Lp,
+                      const int32_t* chosen, hipStream_t s) {
+  kv_commit_kernel<T><<<dim3(g.L, g.B), 256, 0, s>>>(kb, vbT, poolK, poolV, g, md.Hkv, md.hd, Lp, chosen);
 }
 template void launch_kv_commit<float>(const float*, const float*, float*, float*, const BatchGeom&, const ModelDims&,
                                       int, const int32_t*, hipStream_t);
@@ -233,38 +261,38 @@ template void launch_prm_head<bf16_t>(const float*, const float*, const bf16_t*,
                                       hipStream_t);
 
 // ---------------------------------------------------------------- log-softmax merge + block sum
-// One block of 64*ceil(L/1) ... : grid = B*n blocks, each wave handles rows t = wave, wave+4, ...
-// Row: merge the per-tile (max, sum exp) partials in tile order, tok_logp = z[y] - (max + log sum).
-// Then thread 0 adds the L token terms in index order (fixed order => run-to-run identical).
+// Kernel 1, one wavefront per row: merge the per-tile (max, sum exp) partials,
+// tok_logp = z[y] - (max + log sum). Kernel 2, one thread per candidate: add its L token terms in
+// index order (fixed order => run-to-run identical), in double because the sum reaches ~1e3.
 __global__ void lmhead_merge_kernel(const float* __restrict__ part_max, const float* __restrict__ part_sum,
-                                    const float* __restrict__ zt, int n_tiles, float* __restrict__ tok_logp,
-                                    float* __restrict__ block_out, int L) {
-  extern __shared__ float lp[];   // [L]
-  size_t c = blockIdx.x;
+                                    const float* __restrict__ zt, int n_tiles, float* __restrict__ tok_logp, int M) {
   int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  for (int t = wave; t < L; t += 4) {
-    size_t m = c * L + t;
-    const float* pm = part_max + m * n_tiles;
-    const float* ps = part_sum + m * n_tiles;
-    float mx = -INFINITY;
-    for (int j = lane; j < n_tiles; j += 64) mx = fmaxf(mx, pm[j]);
-    mx = wave_max(mx);
-    float sm = 0.f;
-    for (int j = lane; j < n_tiles; j += 64) sm += ps[j] * expf(pm[j] - mx);
-    sm = wave_sum(sm);
-    if (lane == 0) lp[t] = (float)((double)zt[m] - ((double)mx + log((double)sm)));
-  }
-  __syncthreads();
-  if (tok_logp)
-    for (int t = threadIdx.x; t < L; t += blockDim.x) tok_logp[c * L + t] = lp[t];
-  if (threadIdx.x == 0) {
-    double acc = 0.0;   // the block sum reaches ~1e3 in magnitude: add the float terms in double, round once
-    for (int t = 0; t < L; ++t) acc += (double)lp[t];
-    block_out[c] = (float)acc;
-  }
+  size_t m = (size_t)blockIdx.x * 4 + wave;
+  if (m >= (size_t)M) return;
+  const float* pm = part_max + m * n_tiles;
+  const float* ps = part_sum + m * n_tiles;
+  float mx = -INFINITY;
+  for (int j = lane; j < n_tiles; j += 64) mx = fmaxf(mx, pm[j]);
+  mx = wave_max(mx);
+  float sm = 0.f;
+  for (int j = lane; j < n_tiles; j += 64) sm += ps[j] * expf(pm[j] - mx);
+  sm = wave_sum(sm);
+  if (lane == 0) tok_logp[m] = (float)((double)zt[m] - ((double)mx + log((double)sm)));
 }
+
+__global__ void block_sum_kernel(const float* __restrict__ tok_logp, float* __restrict__ block_out, int L, int C) {
+  int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  double acc = 0.0;
+  for (int t = 0; t < L; ++t) acc += (double)tok_logp[(size_t)c * L + t];
+  block_out[c] = (float)acc;
+}
+
+// tok_scratch: [M] floats used when the caller does not want the per-token terms
 void launch_lmhead_merge(const float* part_max, const float* part_sum, const float* zt, int n_tiles, float* tok_logp,
-                         float* block_out, const BatchGeom& g, hipStream_t s) {
-  lmhead_merge_kernel<<<g.B * g.n, 256, g.L * sizeof(float), s>>>(part_max, part_sum, zt, n_tiles, tok_logp, block_out,
-                                                                 g.L);
+                         float* tok_scratch, float* block_out, const BatchGeom& g, hipStream_t s) {
+  float* tl = tok_logp ? tok_logp : tok_scratch;
+  lmhead_merge_kernel<<<(g.M + 3) / 4, 256, 0, s>>>(part_max, part_sum, zt, n_tiles, tl, g.M);
+  int C = g.B * g.n;
+  block_sum_kernel<<<(C + 63) / 64, 64, 0, s>>>(tl, block_out, g.L, C);
 }

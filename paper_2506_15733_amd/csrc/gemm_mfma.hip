@@ -37,21 +37,18 @@ struct GemmArgs {
   float* zt;             // ME_LMHEAD: [M]
 };
 
-template <int ROWS>
-__device__ __forceinline__ void load_tile_async(const bf16_t* __restrict__ G, int row0, int rows_total, int K, int k0,
-                                                char* lds_tile) {
+// One direct-to-LDS load instruction: span p (8 wavefronts x 1 KiB = 64 rows of 128 bytes) of an operand tile.
+__device__ __forceinline__ void load_span_async(const bf16_t* __restrict__ G, int row0, int rows_total, int K, int k0,
+                                                char* lds_tile, int p) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-#pragma unroll
-  for (int p = 0; p < ROWS / 64; ++p) {
-    int span = p * 8 + wave;                 // 1 KiB of LDS = 8 rows, written by one wavefront
-    int q = span * 64 + lane;
-    int row = q >> 3, slot = q & 7;
-    int chunk = slot ^ ((row >> 1) & 7);
-    int grow = row0 + row;
-    grow = grow < rows_total ? grow : rows_total - 1;
-    const bf16_t* src = G + (size_t)grow * K + k0 + chunk * 8;
-    __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(lds_tile + span * 1024), 16, 0, 0);
-  }
+  int span = p * 8 + wave;                   // 1 KiB of LDS = 8 rows, written by one wavefront
+  int q = span * 64 + lane;
+  int row = q >> 3, slot = q & 7;
+  int chunk = slot ^ ((row >> 1) & 7);
+  int grow = row0 + row;
+  grow = grow < rows_total ? grow : rows_total - 1;
+  const bf16_t* src = G + (size_t)grow * K + k0 + chunk * 8;
+  __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(lds_tile + span * 1024), 16, 0, 0);
 }
 
 __device__ __forceinline__ bf16x8 lds_frag(const char* tile, int row, int chunk) {
@@ -86,32 +83,72 @@ __global__ void __launch_bounds__(512) gemm_mfma_kernel(GemmArgs a) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int KT = a.K / 64;
-  load_tile_async<BM>(a.A, m0, a.M, a.K, 0, smem);
-  load_tile_async<BN>(a.W, n0, a.N, a.K, 0, smem + A_BYTES);
-  for (int kt = 0; kt < KT; ++kt) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 1 < KT) {
-      char* nxt = smem + ((kt + 1) & 1) * STAGE;
-      load_tile_async<BM>(a.A, m0, a.M, a.K, (kt + 1) * 64, nxt);
-      load_tile_async<BN>(a.W, n0, a.N, a.K, (kt + 1) * 64, nxt + A_BYTES);
-    }
-    const char* As = smem + (kt & 1) * STAGE;
+  auto read_frags = [&](const char* As, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
     const char* Bs = As + A_BYTES;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 af[TM], bfr[TN];
+    for (int i = 0; i < TM; ++i) af[i] = lds_frag(As, wm * WM + i * 32 + lrow, ks * 2 + lhalf);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = lds_frag(As, wm * WM + i * 32 + lrow, ks * 2 + lhalf);
+    for (int j = 0; j < TN; ++j) bfr[j] = lds_frag(Bs, wn * 64 + j * 32 + lrow, ks * 2 + lhalf);
+  };
+  auto mma = [&](const bf16x8 (&af)[TM], const bf16x8 (&bfr)[TN]) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[j] = lds_frag(Bs, wn * 64 + j * 32 + lrow, ks * 2 + lhalf);
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+  };
+  constexpr int LA = BM / 64, LB = BN / 64, LPT = LA + LB;   // direct-to-LDS loads per thread per K-tile
+  // load instruction i (0 .. LPT-1) of K-tile t into ring buffer `buf`
+  auto issue = [&](int i, int t, char* buf) {
+    if (i < LA) load_span_async(a.A, m0, a.M, a.K, t * 64, buf, i);
+    else load_span_async(a.W, n0, a.N, a.K, t * 64, buf + A_BYTES, i - LA);
+  };
+  // One k-step of the software pipeline: two MFMAs of the current group go first, then the LDS reads of the
+  // next group (and, in the first k-step, the next K-tile's global loads) are issued, then the rest of the
+  // MFMAs. Nothing in the group waits on those reads.
+#define PIPE_STEP_ORDER(NLOADS)                                        \
+  __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                   \
+  __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);             \
+  __builtin_amdgcn_sched_group_barrier(0x010, NLOADS, 0);              \
+  __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - 2, 0);         \
+  __builtin_amdgcn_sched_barrier(0)
+
+  constexpr int L0 = LPT, L1 = 0, L2 = 0;
+
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
+  for (int i = 0; i < LPT; ++i) issue(i, 0, smem);
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+  bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
+  read_frags(smem, 0, a0, b0);
+  for (int kt = 0; kt < KT; ++kt) {
+    const char* cur = smem + (kt & 1) * STAGE;
+    char* nxt = smem + ((kt + 1) & 1) * STAGE;
+    // The loop body is branch-free so that each k-step stays one scheduling region: on the last K-tile the
+    // "next" tile is the last one again (a redundant reload into the free buffer, never consumed).
+    const int tn = kt + 1 < KT ? kt + 1 : KT - 1;
+    // every wavefront is past the barrier that ended K-tile kt-1, so its buffer (nxt) is free
+    read_frags(cur, 1, a1, b1);
+#pragma unroll
+    for (int i = 0; i < L0; ++i) issue(i, tn, nxt);
+    mma(a0, b0);
+    PIPE_STEP_ORDER(L0);
+    read_frags(cur, 2, a0, b0);
+#pragma unroll
+    for (int i = L0; i < L0 + L1; ++i) issue(i, tn, nxt);
+    mma(a1, b1);
+    PIPE_STEP_ORDER(L1);
+    read_frags(cur, 3, a1, b1);
+#pragma unroll
+    for (int i = L0 + L1; i < LPT; ++i) issue(i, tn, nxt);
+    mma(a0, b0);
+    PIPE_STEP_ORDER(L2);
+    // publish K-tile kt+1: own loads landed, own reads of K-tile kt complete, then meet the other wavefronts
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    read_frags(nxt, 0, a0, b0);
+    mma(a1, b1);
+    PIPE_STEP_ORDER(0);
   }
+#undef PIPE_STEP_ORDER
 
   // accumulator element r of lane: row 8*(r/4) + 4*lhalf + r%4, column lrow of the 32x32 tile
   if (EPI == ME_STORE || EPI == ME_RESIDUAL) {

@@ -44,18 +44,23 @@ struct Workspace {
   char* q;           // [R, Hq*hd] (T)
   char* attn;        // [R, Hq*hd] (T)
   char* kblk;        // [n_layers][R, Hkv*hd] (T)
-  char* vblk;
+  char* vblk;        // [n_layers][C, Hkv*hd, Lp] transposed block values
   float* gu;         // [R, 2F]
   char* act;         // [R, F] (T)
   float* cs;         // [R, hd] cos | sin
   float* part_max;   // [R, tiles]
   float* part_sum;
   float* zt;         // [R]
+  float* tokl;       // [R] per-token log-probs when the caller passes no buffer
   int32_t* chosen;   // [B]
   size_t total;
 };
 
-static Workspace carve(char* base, const specs_model_desc& d, int64_t R, int B) {
+static inline int round16(int v) { return (v + 15) & ~15; }
+
+// R rows in C = B*n candidate blocks. Block values are kept transposed with the block length padded
+// to a multiple of 16, hence up to R + 16*C value columns per layer.
+static Workspace carve(char* base, const specs_model_desc& d, int64_t R, int64_t C) {
   Workspace w;
   size_t off = 0, es = esize(d.dtype);
   auto take = [&](size_t bytes) { char* p = base ? base + off : nullptr; off += align256(bytes); return p; };
@@ -68,7 +73,7 @@ static Workspace carve(char* base, const specs_model_desc& d, int64_t R, int B) 
   w.q = take(R * qd * es);
   w.attn = take(R * qd * es);
   w.kblk = take((size_t)d.n_layers * R * kvd * es);
-  w.vblk = take((size_t)d.n_layers * R * kvd * es);
+  w.vblk = take((size_t)d.n_layers * (R + 16 * C) * kvd * es);
   w.gu = (float*)take(R * 2 * (size_t)d.ffn * 4);
   w.act = take(R * (size_t)d.ffn * es);
   w.cs = (float*)take(R * d.head_dim * 4);
@@ -76,7 +81,8 @@ static Workspace carve(char* base, const specs_model_desc& d, int64_t R, int B) 
   w.part_max = (float*)take(R * tiles * 4);
   w.part_sum = (float*)take(R * tiles * 4);
   w.zt = (float*)take(R * 4);
-  w.chosen = (int32_t*)take((size_t)(B > 0 ? B : 1) * 4);
+  w.tokl = (float*)take(R * 4);
+  w.chosen = (int32_t*)take((size_t)(C > 0 ? C : 1) * 4);
   w.total = off;
   return w;
 }
@@ -105,9 +111,9 @@ static bool desc_ok(const specs_model_desc& d) {
   return true;
 }
 
-extern "C" size_t specs_workspace_bytes(const specs_model_desc* desc, int64_t max_rows, int32_t max_B) {
-  if (!desc || max_rows <= 0 || max_B <= 0 || !desc_ok(*desc)) return 0;
-  return carve(nullptr, *desc, max_rows, max_B).total;
+extern "C" size_t specs_workspace_bytes(const specs_model_desc* desc, int64_t max_rows, int32_t max_blocks) {
+  if (!desc || max_rows <= 0 || max_blocks <= 0 || !desc_ok(*desc)) return 0;
+  return carve(nullptr, *desc, max_rows, max_blocks).total;
 }
 
 extern "C" int specs_ctx_create(int device, void* hip_stream, void* workspace, size_t workspace_bytes, specs_ctx** out) {
@@ -255,8 +261,8 @@ int lmhead_partials<bf16_t>(const bf16_t* A, const bf16_t* W, const int32_t* tok
 }
 
 template <typename T>
-static void attention(const T* q, const T* kb, const T* vb, const T* pK, const T* pV, T* out, const BatchGeom& g,
-                      const ModelDims& md, int max_ctx, hipStream_t s);
+static void attention(const T* q, const T* kb, const T* vbT, const T* pK, const T* pV, T* out, const BatchGeom& g,
+                      const ModelDims& md, int Lp, int max_ctx, hipStream_t s);
 
 // The trunk over M = B*n*L rows: every row attends to its beam's cached prefix and causally
 // to the earlier rows of its own block. Leaves the final residual stream in ws.x and the
@@ -264,23 +270,24 @@ static void attention(const T* q, const T* kb, const T* vb, const T* pK, const T
 // prefix pages (prefill).
 template <typename T>
 static void run_trunk(const specs_model* m, const specs_prefix* p, const Workspace& ws, const BatchGeom& g,
-                      const int32_t* tokens, int max_ctx, bool commit_pages, int64_t R, hipStream_t s) {
+                      const int32_t* tokens, int max_ctx, bool commit_pages, int64_t R, int64_t C, hipStream_t s) {
   const specs_model_desc& d = m->desc;
   ModelDims md = dims_of(d);
+  const int Lp = round16(g.L);
   int qd = md.Hq * md.hd, kvd = md.Hkv * md.hd;
   launch_embed<T>(tokens, (const T*)m->w.embed, ws.x, g.M, md.d, md.V, ws.status, s);
   launch_rope_table(ws.cs, g, md.hd, md.rope_base, s);
   for (int l = 0; l < d.n_layers; ++l) {
     const specs_layer_weights& L = m->layers[l];
     T* kb = (T*)ws.kblk + (size_t)l * R * kvd;
-    T* vb = (T*)ws.vblk + (size_t)l * R * kvd;
+    T* vb = (T*)ws.vblk + (size_t)l * (R + 16 * C) * kvd;
     T* pK = pool_ptr<T>(p, d, l, 0);
     T* pV = pool_ptr<T>(p, d, l, 1);
     launch_rmsnorm<T>(ws.x, L.g_attn, (T*)ws.a, g.M, md.d, md.eps, s);
     gemm<T>((const T*)ws.a, (const T*)L.wqkv, ws.qkv, g.M, qd + 2 * kvd, md.d, EPI_STORE_F32, s);
-    launch_rope_split<T>(ws.qkv, ws.cs, (T*)ws.q, kb, vb, g.M, md, s);
-    attention<T>((const T*)ws.q, kb, vb, pK, pV, (T*)ws.attn, g, md, max_ctx, s);
-    if (commit_pages) launch_kv_commit<T>(kb, vb, pK, pV, g, md, 0, nullptr, s);
+    launch_rope_split<T>(ws.qkv, ws.cs, (T*)ws.q, kb, vb, g, Lp, md, s);
+    attention<T>((const T*)ws.q, kb, vb, pK, pV, (T*)ws.attn, g, md, Lp, max_ctx, s);
+    if (commit_pages) launch_kv_commit<T>(kb, vb, pK, pV, g, md, Lp, nullptr, s);
     gemm<T>((const T*)ws.attn, (const T*)L.wo, ws.x, g.M, md.d, qd, EPI_RESIDUAL_ADD, s);
     launch_rmsnorm<T>(ws.x, L.g_ffn, (T*)ws.a, g.M, md.d, md.eps, s);
     gate_up<T>((const T*)ws.a, (const T*)L.wgu, ws.gu, (T*)ws.act, g.M, md.F, md.d, s);
@@ -293,7 +300,8 @@ static int score_impl(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
                       float* out, float* tok_logp) {
   const specs_model_desc& d = m->desc;
   int64_t R = (int64_t)p->B * n * L;
-  Workspace ws = carve(ctx->workspace, d, R, p->B);
+  int64_t C = (int64_t)p->B * n;
+  Workspace ws = carve(ctx->workspace, d, R, C);
   if (ws.total > ctx->workspace_bytes) return SPECS_EWORKSPACE;
   BatchGeom g;
   g.B = p->B; g.n = n; g.L = L; g.M = (int)R; g.b0 = 0; g.len_override = -1;
@@ -301,12 +309,12 @@ static int score_impl(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
   int max_ctx = 0;
   for (int b = 0; b < p->B; ++b) max_ctx = p->lens[b] > max_ctx ? p->lens[b] : max_ctx;
   hipStream_t s = ctx->stream;
-  run_trunk<T>(m, p, ws, g, cand, max_ctx, false, R, s);
+  run_trunk<T>(m, p, ws, g, cand, max_ctx, false, R, C, s);
   if (d.head == SPECS_HEAD_LM) {
     launch_rmsnorm_shifted<T>(ws.x, p->h_last, m->w.g_final, (T*)ws.a, g, d.d_model, d.rms_eps, s);
     int tiles = lmhead_partials<T>((const T*)ws.a, (const T*)m->w.head, cand, ws.part_max, ws.part_sum, ws.zt, g.M,
                                    d.vocab, d.d_model, s);
-    launch_lmhead_merge(ws.part_max, ws.part_sum, ws.zt, tiles, tok_logp, out, g, s);
+    launch_lmhead_merge(ws.part_max, ws.part_sum, ws.zt, tiles, tok_logp, ws.tokl, out, g, s);
   } else {
     launch_prm_head<T>(ws.x, m->w.g_final, (const T*)m->w.head, out, g, d.d_model, d.rms_eps, s);
   }
@@ -351,7 +359,7 @@ static int prefill_impl(specs_ctx* ctx, const specs_model* m, specs_prefix* p, c
       BatchGeom g;
       g.B = 1; g.n = 1; g.L = rows; g.M = rows; g.b0 = b; g.len_override = c0;
       g.lens = p->lens_dev; g.page_table = p->page_table; g.max_pages = p->max_pages; g.page_tokens = p->page_tokens;
-      run_trunk<T>(m, p, ws, g, tokens + off + c0, c0, true, R, s);
+      run_trunk<T>(m, p, ws, g, tokens + off + c0, c0, true, R, 1, s);
       if (c0 + rows == len) launch_copy_rows(ws.x, p->h_last, g, d.d_model, nullptr, s);
     }
     off += len;
@@ -379,8 +387,8 @@ template <typename T>
 static int commit_impl(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* chosen_host) {
   const specs_model_desc& d = m->desc;
   int n = ctx->last_n, L = ctx->last_L;
-  int64_t R = (int64_t)p->B * n * L;
-  Workspace ws = carve(ctx->workspace, d, R, p->B);
+  int64_t R = (int64_t)p->B * n * L, C = (int64_t)p->B * n;
+  Workspace ws = carve(ctx->workspace, d, R, C);
   ModelDims md = dims_of(d);
   hipStream_t s = ctx->stream;
   HIP_TRY(hipMemcpyAsync(ws.chosen, chosen_host, sizeof(int32_t) * p->B, hipMemcpyHostToDevice, s));
@@ -389,8 +397,8 @@ static int commit_impl(specs_ctx* ctx, const specs_model* m, specs_prefix* p, co
   g.lens = p->lens_dev; g.page_table = p->page_table; g.max_pages = p->max_pages; g.page_tokens = p->page_tokens;
   size_t kvd = (size_t)md.Hkv * md.hd;
   for (int l = 0; l < d.n_layers; ++l)
-    launch_kv_commit<T>((const T*)ws.kblk + (size_t)l * R * kvd, (const T*)ws.vblk + (size_t)l * R * kvd,
-                        pool_ptr<T>(p, d, l, 0), pool_ptr<T>(p, d, l, 1), g, md, 0, ws.chosen, s);
+    launch_kv_commit<T>((const T*)ws.kblk + (size_t)l * R * kvd, (const T*)ws.vblk + (size_t)l * (R + 16 * C) * kvd,
+                        pool_ptr<T>(p, d, l, 0), pool_ptr<T>(p, d, l, 1), g, md, round16(L), ws.chosen, s);
   launch_copy_rows(ws.x, p->h_last, g, d.d_model, ws.chosen, s);
   advance_lens_kernel<<<(p->B + 63) / 64, 64, 0, s>>>(p->lens_dev, p->B, L);
   HIP_TRY(hipGetLastError());
@@ -460,26 +468,33 @@ extern "C" int specs_op_lmhead_logprob(specs_ctx* ctx, int32_t dtype, const void
   if (dtype != SPECS_F32 && dtype != SPECS_BF16) return SPECS_EINVAL;
   size_t tiles = (size_t)lmhead_simple_tiles(V);
   size_t per = align256((size_t)M * tiles * 4);
-  if (256 + 2 * per + align256((size_t)M * 4) > ctx->workspace_bytes) return SPECS_EWORKSPACE;
+  if (256 + 2 * per + 2 * align256((size_t)M * 4) > ctx->workspace_bytes) return SPECS_EWORKSPACE;
   float* pm = (float*)(ctx->workspace + 256);
   float* ps = (float*)(ctx->workspace + 256 + per);
   float* zt = (float*)(ctx->workspace + 256 + 2 * per);
+  float* tl = (float*)(ctx->workspace + 256 + 2 * per + align256((size_t)M * 4));
   HIP_TRY(hipSetDevice(ctx->device));
   int nt = dtype == SPECS_BF16
                ? lmhead_partials<bf16_t>((const bf16_t*)A, (const bf16_t*)W, tok, pm, ps, zt, M, V, K, ctx->stream)
                : lmhead_partials<float>((const float*)A, (const float*)W, tok, pm, ps, zt, M, V, K, ctx->stream);
   BatchGeom g = {};
   g.B = 1; g.n = M; g.L = 1; g.M = M;
-  launch_lmhead_merge(pm, ps, zt, nt, nullptr, tok_logp, g, ctx->stream);
+  launch_lmhead_merge(pm, ps, zt, nt, nullptr, tl, tok_logp, g, ctx->stream);
   HIP_TRY(hipGetLastError());
   ctx->last_model = nullptr;
   return SPECS_OK;
 }
 
 template <typename T>
-static void attention(const T* q, const T* kb, const T* vb, const T* pK, const T* pV, T* out, const BatchGeom& g,
-                      const ModelDims& md, int max_ctx, hipStream_t s) {
-  launch_attention_simple<T>(q, kb, vb, pK, pV, out, g, md, max_ctx, s);
+static void attention(const T* q, const T* kb, const T* vbT, const T* pK, const T* pV, T* out, const BatchGeom& g,
+                      const ModelDims& md, int Lp, int max_ctx, hipStream_t s) {
+  launch_attention_simple<T>(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, s);
+}
+template <>
+void attention<bf16_t>(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT, const bf16_t* pK, const bf16_t* pV,
+                       bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp, int max_ctx, hipStream_t s) {
+  if (!launch_attention_mfma(q, kb, vbT, pK, pV, out, g, md, Lp, s))
+    launch_attention_simple<bf16_t>(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, s);
 }
 
 extern "C" int specs_op_attention(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, int32_t layer,
@@ -493,14 +508,22 @@ extern "C" int specs_op_attention(specs_ctx* ctx, const specs_model* m, const sp
   int max_ctx = 0;
   for (int b = 0; b < p->B; ++b) max_ctx = p->lens[b] > max_ctx ? p->lens[b] : max_ctx;
   ModelDims md = dims_of(d);
+  const int Lp = round16(L), cands = p->B * n;
+  size_t vt_bytes = (size_t)cands * md.Hkv * md.hd * Lp * esize(d.dtype);
+  if (256 + align256(vt_bytes) > ctx->workspace_bytes) return SPECS_EWORKSPACE;
+  char* vT = ctx->workspace + 256;
   HIP_TRY(hipSetDevice(ctx->device));
-  if (d.dtype == SPECS_BF16)
-    attention<bf16_t>((const bf16_t*)q, (const bf16_t*)kb, (const bf16_t*)vb, pool_ptr<bf16_t>(p, d, layer, 0),
-                      pool_ptr<bf16_t>(p, d, layer, 1), (bf16_t*)out, g, md, max_ctx, ctx->stream);
-  else
-    attention<float>((const float*)q, (const float*)kb, (const float*)vb, pool_ptr<float>(p, d, layer, 0),
-                     pool_ptr<float>(p, d, layer, 1), (float*)out, g, md, max_ctx, ctx->stream);
+  if (d.dtype == SPECS_BF16) {
+    launch_transpose_v<bf16_t>((const bf16_t*)vb, (bf16_t*)vT, cands, md.Hkv, md.hd, L, Lp, ctx->stream);
+    attention<bf16_t>((const bf16_t*)q, (const bf16_t*)kb, (const bf16_t*)vT, pool_ptr<bf16_t>(p, d, layer, 0),
+                      pool_ptr<bf16_t>(p, d, layer, 1), (bf16_t*)out, g, md, Lp, max_ctx, ctx->stream);
+  } else {
+    launch_transpose_v<float>((const float*)vb, (float*)vT, cands, md.Hkv, md.hd, L, Lp, ctx->stream);
+    attention<float>((const float*)q, (const float*)kb, (const float*)vT, pool_ptr<float>(p, d, layer, 0),
+                     pool_ptr<float>(p, d, layer, 1), (float*)out, g, md, Lp, max_ctx, ctx->stream);
+  }
   HIP_TRY(hipGetLastError());
+  ctx->last_model = nullptr;
   return SPECS_OK;
 }
 

@@ -22,7 +22,7 @@ def pack_gate_up(wg, wu):
 class DeviceModel:
     """Weights of one model in device memory + its ABI handles (context with own workspace, model)."""
 
-    def __init__(self, desc, device, stream, max_rows, max_B, seed=0):
+    def __init__(self, desc, device, stream, max_rows, max_blocks, seed=0):
         self.desc, self.device = desc, device
         top, per_layer = weight_shapes(desc)
         gen = lambda name, shape: device_tensor(desc, seed, name, shape, device)
@@ -38,7 +38,7 @@ class DeviceModel:
             del wg, wu
         self.cdesc = B.make_desc(desc.n_layers, desc.d_model, desc.n_q_heads, desc.n_kv_heads, desc.head_dim, desc.ffn,
                                  desc.vocab, desc.dtype, desc.head, desc.rope_base, desc.rms_eps)
-        nbytes = B.specs_workspace_bytes(self.cdesc, max_rows, max_B)
+        nbytes = B.specs_workspace_bytes(self.cdesc, max_rows, max_blocks)
         assert nbytes > 0
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
         self.ctx = B.specs_ctx_create(torch.device(device).index or 0, stream.cuda_stream, self.workspace)
@@ -55,7 +55,8 @@ class DevicePrefix:
     def __init__(self, dm: DeviceModel, lens, page_table, num_pages, page_tokens):
         d, dev = dm.desc, dm.device
         tdt = torch.bfloat16 if d.dtype == "bf16" else torch.float32
-        self.kv_pool = torch.zeros((d.n_layers, 2, num_pages, d.n_kv_heads, page_tokens, d.head_dim), dtype=tdt, device=dev)
+        # [layer][K|V][page][kv head][page_tokens*head_dim]; K page-heads are [token][dim], V page-heads [dim][token]
+        self.kv_pool = torch.zeros((d.n_layers, 2, num_pages, d.n_kv_heads, page_tokens * d.head_dim), dtype=tdt, device=dev)
         self.page_table = torch.from_numpy(np.ascontiguousarray(page_table)).to(dev)
         self.lens_host = [int(x) for x in lens]
         self.lens_dev = torch.tensor(self.lens_host, dtype=torch.int32, device=dev)
@@ -82,7 +83,7 @@ class ScoringStep:
         table, num_pages = wl.page_table(extra_tokens)
         self.models, self.prefixes = {}, {}
         for role, desc in wl.models().items():
-            self.models[role] = DeviceModel(desc, device, self.stream, rows, wl.B, wl.seed)
+            self.models[role] = DeviceModel(desc, device, self.stream, rows, wl.B * wl.n, wl.seed)
             self.prefixes[role] = DevicePrefix(self.models[role], lens, table, num_pages, wl.page_tokens)
         self.cand = torch.from_numpy(wl.candidates()).to(device)
         self.prefix_tokens = torch.from_numpy(np.concatenate(wl.prefix_tokens()).astype(np.int32)).to(device)

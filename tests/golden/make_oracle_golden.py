@@ -4,8 +4,14 @@ Calls only `oracle` (and the input generators in `workload`); nothing here touch
 The large configurations take minutes (c3) to an hour (c4) of float64 BLAS time, which is why
 their expected values are stored instead of being recomputed inside the GPU test run.
 
-usage: python tests/golden/make_oracle_golden.py c3_1p5b [--beams 0,1]
+With --noise it also evaluates every role WITHOUT operand rounding (same bf16-valued weights, all
+arithmetic float64) and stores how far that moves the outputs: the sensitivity of the result to the
+bf16 rounding of matrix operands, i.e. the floor under which no two bf16 evaluations can be expected to
+agree. The GPU parity test scales its tolerance by it.
+
+usage: python tests/golden/make_oracle_golden.py c3_1p5b [--beams 0,1] [--noise]
 """
+import dataclasses
 import argparse
 import json
 import os
@@ -26,6 +32,7 @@ def main():
     ap.add_argument("config")
     ap.add_argument("--beams", default=None, help="comma-separated beam indices (default: all)")
     ap.add_argument("--roles", default="target,draft,prm")
+    ap.add_argument("--noise", action="store_true")
     args = ap.parse_args()
     wl = W.get_config(args.config)
     beams = list(range(wl.B)) if args.beams is None else [int(b) for b in args.beams.split(",")]
@@ -52,6 +59,17 @@ def main():
             out[role] = res[0].tolist()
             out["tok_" + role] = res[1].tolist()
         out[f"seconds_{role}"] = {"prefill": round(t1 - t0, 1), "score": round(t2 - t1, 1)}
+        if args.noise:
+            exact = dataclasses.replace(desc, dtype="f32")      # no rounding points; weights stay bf16-valued
+            res_x = oracle.score_cached(exact, hw, oracle.prefill(exact, hw, pt), cand)
+            if desc.head == "prm":
+                out[f"noise_{role}"] = {"max": float(np.abs(np.asarray(res_x) - np.asarray(res)).max())}
+            else:
+                dt, db = res_x[1] - res[1], res_x[0] - res[0]
+                out[f"noise_{role}"] = {"tok_rms": float(np.sqrt((dt ** 2).mean())), "tok_max": float(np.abs(dt).max()),
+                                        "block_rms": float(np.sqrt((db ** 2).mean())),
+                                        "block_max": float(np.abs(db).max())}
+            print(role, "noise", out[f"noise_{role}"], flush=True)
         print(role, out[f"seconds_{role}"], flush=True)
         json.dump(out, open(path, "w"))
     print("wrote", path)

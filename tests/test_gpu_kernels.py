@@ -79,11 +79,12 @@ def test_gate_up_bf16(ctx, M, F, K):
     got = act.float().cpu().numpy().astype(np.float64)
     exact = oracle.silu(oracle.linear(a, wg)) * oracle.linear(a, wu)
     want = oracle.round_bf16(exact)
-    # identical except where float accumulation order moves a value across a bf16 rounding boundary
-    ulp = np.abs(want) * 2.0 ** -7 + 1e-30
-    assert np.all(np.abs(got - want) <= ulp)
-    assert (got != want).mean() < 2e-3
-    close(got, exact, 4e-3)
+    # identical except where float accumulation order moves a value across a bf16 rounding boundary:
+    # never more than one bf16 step (plus the float accumulation error itself for values near zero)
+    rms = np.sqrt((exact ** 2).mean())
+    assert np.all(np.abs(got - want) <= np.abs(want) * 2.0 ** -7 + 1e-4 * rms)
+    assert (got != want).mean() < 5e-3
+    assert np.all(np.abs(got - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-4 * rms)
 
 
 @pytest.mark.parametrize("M,V,K", [(45, 301, 64), (100, 1000, 128), (256, 32768, 1024), (512, 152064, 3584)])
@@ -129,6 +130,9 @@ def attention_case(ctx, desc, Bn, n, L, lens, page_tokens, sample_rows=None):
     kb, tkb = draw("akb", (M, Hkv, hd), 1.0, desc.dtype)
     vb, tvb = draw("avb", (M, Hkv, hd), 1.0, desc.dtype)
     pool, tpool = draw("apool", (1, 2, num_pages, Hkv, page_tokens, hd), 1.0, desc.dtype)
+    # device layout: key page-heads [token][dim], value page-heads transposed [dim][token]
+    tpool = torch.stack([tpool[:, 0].reshape(1, num_pages, Hkv, -1),
+                         tpool[:, 1].transpose(-1, -2).reshape(1, num_pages, Hkv, -1)], dim=1).contiguous()
     cdesc = B.make_desc(1, desc.d_model, Hq, Hkv, hd, desc.ffn, desc.vocab, desc.dtype, "prm")
     dummy = torch.zeros(max(desc.d_model, 64), dtype=tdt, device=DEV)
     ones = torch.ones(desc.d_model, dtype=torch.float32, device=DEV)

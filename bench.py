@@ -17,6 +17,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM-side bytes per launch of the dominant kernel from two rocprofv3 --pmc runs (FETCH_SIZE x2.00 + WRITE_SIZE x1.00,
+# factors from a 1 GiB device copy); summary in profiles/gemm_gate_up_and_attention_c4_7b_pmc.md
+MEASURED_TRAFFIC_BYTES = {"c4_7b": 859.1e6 + 77.6e6}
 
 
 def role_flops(d, M, P_total_rows_ctx, n, L, B):
@@ -111,6 +114,10 @@ def kernel_bench(args):
         out = torch.empty((M, qd), dtype=torch.bfloat16, device=dev)
         fn = lambda: B.specs_op_attention(ctx, model, prefix, 0, q, kb, vb, wl.n, wl.L, out)
         flops = 4.0 * qd * (sum(l * wl.n * wl.L for l in lens) + wl.B * wl.n * wl.L * (wl.L + 1) / 2.0)
+    elif k == "copy":
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written per launch
+        dst = torch.empty_like(src)
+        fn, flops = (lambda: dst.copy_(src)), 0.0
     else:
         raise SystemExit(f"unknown kernel {k}")
     for _ in range(3):
@@ -128,7 +135,7 @@ def kernel_bench(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--kernel", default=None, help="gate_up|qkv|o|down|lmhead|attn: time that kernel alone")
+    ap.add_argument("--kernel", default=None, help="gate_up|qkv|o|down|lmhead|attn|copy: time that kernel alone")
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
@@ -173,29 +180,22 @@ def main():
         torch.cuda.synchronize()
         role_ms[r] = e0.elapsed_time(e1) / 3
 
-    # dominant kernel: the fused gate/up SwiGLU GEMM of the target/PRM model, timed on its own
+    # Per-kernel durations inside the real pass: events on the launch stream around every launch of the
+    # target-model scoring call (recorded in extra passes after the timed region, not inside it).
     d = wl.target
     M = wl.B * wl.n * wl.L
     dm = step.models["target"]
-    A = torch.randn((M, d.d_model), device="cuda:0").to(torch.bfloat16)
-    act = torch.empty((M, d.ffn), dtype=torch.bfloat16, device="cuda:0")
-    wgu = dm.layers[0]["wgu"]
-    reps = 20
+    B.specs_ctx_profile(dm.ctx, True)
     for _ in range(3):
-        B.specs_op_gate_up(dm.ctx, A, wgu, act)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
-        B.specs_op_gate_up(dm.ctx, A, wgu, act)
-    e1.record()
-    torch.cuda.synchronize()
-    k_ms = e0.elapsed_time(e1) / reps
+        step.score("target")
+    prof = B.specs_ctx_profile_read(dm.ctx)
+    B.specs_ctx_profile(dm.ctx, False)
+    kernel_us = {k: (1e3 * ms / n if n else 0.0) for k, (ms, n) in prof.items()}
+    # dominant kernel: the fused gate/up SwiGLU GEMM of the target/PRM model
+    k_ms = kernel_us["gate_up"] / 1e3
     flops = 2.0 * M * d.d_model * 2 * d.ffn
     achieved = flops / (k_ms * 1e-3) / 1e12
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(args.workload)
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
 
     lens = wl.prefix_lens()
     ctx_rows = float(sum(int(l) * wl.n * wl.L for l in lens))
@@ -208,7 +208,7 @@ def main():
         "config": {"workload": wl.name, "B": wl.B, "n": wl.n, "L": wl.L, "prefix_tokens": int(lens.sum()),
                    "roles": "target+draft+prm+subsample"},
         "step_tflops": total_flops / dt / 1e12, "step_frac_of_mfma_peak": total_flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-        "role_ms": role_ms,
+        "role_ms": role_ms, "target_kernel_us_per_launch": kernel_us,
         "roofline": {"kernel": "gemm_mfma_kernel<256, SWIGLU> (gate/up projection + SiLU*mul)", "bound": "mfma",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "ms_per_launch": k_ms,

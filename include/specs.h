@@ -100,6 +100,24 @@ int specs_ctx_destroy(specs_ctx* ctx);
  * error since the last call of this function) in *device_status and clears it. */
 int specs_ctx_status(specs_ctx* ctx, int* device_status);
 
+/* Per-kernel timing (HIP events on the context's stream around every launch of the scoring pass, grouped
+ * by kernel class). specs_ctx_profile(ctx, 1) clears the records and switches recording on for the calls
+ * that follow; specs_ctx_profile_read synchronises the stream and returns, per class, the summed duration
+ * in milliseconds and the number of launches since recording was switched on. Recording adds two event
+ * records per launch, so leave it off in timed regions. */
+enum {
+  SPECS_K_QKV = 0,      /* QKV projection */
+  SPECS_K_ATTENTION,    /* shared-prefix attention */
+  SPECS_K_OPROJ,        /* output projection + residual */
+  SPECS_K_GATE_UP,      /* gate/up projection + SiLU*mul */
+  SPECS_K_DOWN,         /* down projection + residual */
+  SPECS_K_LMHEAD,       /* fused vocabulary head partials */
+  SPECS_K_OTHER,        /* embedding, norms, rotary, merges, PRM head */
+  SPECS_K_COUNT
+};
+int specs_ctx_profile(specs_ctx* ctx, int enable);
+int specs_ctx_profile_read(specs_ctx* ctx, float* total_ms, int32_t* launches);
+
 /* Wraps the caller's weights (no copy of tensor data; the per-layer pointer table is copied). */
 int specs_model_create(specs_ctx* ctx, const specs_model_desc* desc, const specs_weights* w, specs_model** out);
 int specs_model_destroy(specs_model* m);

@@ -8,4 +8,5 @@ from .binding import (load_library, SpecsError, specs_workspace_bytes, specs_ctx
                       specs_ctx_status, specs_model_create, specs_model_destroy, specs_prefix_create,
                       specs_prefix_destroy, specs_prefill, specs_score_blocks, specs_commit_block,
                       specs_subsample, specs_strerror, specs_op_linear, specs_op_gate_up,
-                      specs_op_lmhead_logprob, specs_op_attention, ModelDescC, EXPORTED_SYMBOLS)
+                      specs_op_lmhead_logprob, specs_op_attention, specs_ctx_profile, specs_ctx_profile_read,
+                      ModelDescC, EXPORTED_SYMBOLS)

@@ -15,7 +15,9 @@ EXPORTED_SYMBOLS = [
     "specs_model_destroy", "specs_prefix_create", "specs_prefix_destroy", "specs_prefill", "specs_score_blocks",
     "specs_commit_block", "specs_subsample", "specs_strerror",
     "specs_op_linear", "specs_op_gate_up", "specs_op_lmhead_logprob", "specs_op_attention",
+    "specs_ctx_profile", "specs_ctx_profile_read",
 ]
+KERNEL_CLASSES = ("qkv", "attention", "oproj", "gate_up", "down", "lmhead", "other")
 
 SPECS_F32, SPECS_BF16 = 0, 1
 SPECS_HEAD_LM, SPECS_HEAD_PRM = 0, 1
@@ -66,6 +68,8 @@ def load_library():
     lib.specs_score_blocks.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp]
     lib.specs_commit_block.argtypes = [vp, vp, vp, C.POINTER(i32)]
     lib.specs_subsample.argtypes = [vp, vp, vp, vp, vp, i32, i32, C.POINTER(C.c_float), i32, vp, vp, vp]
+    lib.specs_ctx_profile.argtypes = [vp, C.c_int]
+    lib.specs_ctx_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
     lib.specs_op_linear.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, i32]
     lib.specs_op_gate_up.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp]
     lib.specs_op_lmhead_logprob.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, vp]
@@ -125,6 +129,18 @@ def specs_ctx_status(ctx):
     v = C.c_int(0)
     _check(load_library().specs_ctx_status(ctx, C.byref(v)), "specs_ctx_status")
     return v.value
+
+
+def specs_ctx_profile(ctx, enable):
+    _check(load_library().specs_ctx_profile(ctx, 1 if enable else 0), "specs_ctx_profile")
+
+
+def specs_ctx_profile_read(ctx):
+    """{kernel class: (total ms, launches)} since profiling was switched on."""
+    n = len(KERNEL_CLASSES)
+    ms, cnt = (C.c_float * n)(), (C.c_int32 * n)()
+    _check(load_library().specs_ctx_profile_read(ctx, ms, cnt), "specs_ctx_profile_read")
+    return {k: (ms[i], cnt[i]) for i, k in enumerate(KERNEL_CLASSES)}
 
 
 def specs_model_create(ctx, desc, embed, head, g_final, layers):

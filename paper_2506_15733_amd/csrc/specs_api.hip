@@ -87,7 +87,24 @@ static Workspace carve(char* base, const specs_model_desc& d, int64_t R, int64_t
   return w;
 }
 
+struct KernelProfile {
+  bool on = false;
+  std::vector<hipEvent_t> pool;
+  size_t used = 0;
+  struct Rec { int cls; hipEvent_t a, b; };
+  std::vector<Rec> recs;
+  hipEvent_t get() {
+    if (used == pool.size()) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      pool.push_back(e);
+    }
+    return pool[used++];
+  }
+};
+
 struct specs_ctx {
+  KernelProfile prof;
   int device;
   hipStream_t stream;
   char* workspace;
@@ -135,9 +152,47 @@ extern "C" int specs_ctx_create(int device, void* hip_stream, void* workspace, s
 }
 
 extern "C" int specs_ctx_destroy(specs_ctx* ctx) {
+  if (ctx)
+    for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
   delete ctx;
   return SPECS_OK;
 }
+
+extern "C" int specs_ctx_profile(specs_ctx* ctx, int enable) {
+  if (!ctx) return SPECS_EINVAL;
+  HIP_TRY(hipStreamSynchronize(ctx->stream));
+  ctx->prof.on = enable != 0;
+  ctx->prof.used = 0;
+  ctx->prof.recs.clear();
+  return SPECS_OK;
+}
+
+extern "C" int specs_ctx_profile_read(specs_ctx* ctx, float* total_ms, int32_t* launches) {
+  if (!ctx || !total_ms || !launches) return SPECS_EINVAL;
+  HIP_TRY(hipStreamSynchronize(ctx->stream));
+  for (int c = 0; c < SPECS_K_COUNT; ++c) { total_ms[c] = 0.f; launches[c] = 0; }
+  for (const KernelProfile::Rec& r : ctx->prof.recs) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
+    total_ms[r.cls] += ms;
+    launches[r.cls] += 1;
+  }
+  return SPECS_OK;
+}
+
+// Runs `stmt` (kernel launches on stream s), bracketed by events of class `cls` when profiling is on.
+#define PROFILED(ctx, cls, s, stmt)                                   \
+  do {                                                                \
+    if ((ctx)->prof.on) {                                             \
+      hipEvent_t e0_ = (ctx)->prof.get(), e1_ = (ctx)->prof.get();    \
+      if (e0_ && e1_) {                                               \
+        (void)hipEventRecord(e0_, s);                                 \
+        stmt;                                                         \
+        (void)hipEventRecord(e1_, s);                                 \
+        (ctx)->prof.recs.push_back({cls, e0_, e1_});                  \
+      } else { stmt; }                                                \
+    } else { stmt; }                                                  \
+  } while (0)
 
 extern "C" int specs_ctx_status(specs_ctx* ctx, int* device_status) {
   if (!ctx || !device_status) return SPECS_EINVAL;
@@ -269,29 +324,35 @@ static void attention(const T* q, const T* kb, const T* vbT, const T* pK, const 
 // per-layer block keys/values in ws.kblk / ws.vblk. commit_pages: also write them into the
 // prefix pages (prefill).
 template <typename T>
-static void run_trunk(const specs_model* m, const specs_prefix* p, const Workspace& ws, const BatchGeom& g,
-                      const int32_t* tokens, int max_ctx, bool commit_pages, int64_t R, int64_t C, hipStream_t s) {
+static void run_trunk(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const Workspace& ws,
+                      const BatchGeom& g, const int32_t* tokens, int max_ctx, bool commit_pages, int64_t R, int64_t C,
+                      hipStream_t s) {
   const specs_model_desc& d = m->desc;
   ModelDims md = dims_of(d);
   const int Lp = round16(g.L);
   int qd = md.Hq * md.hd, kvd = md.Hkv * md.hd;
-  launch_embed<T>(tokens, (const T*)m->w.embed, ws.x, g.M, md.d, md.V, ws.status, s);
-  launch_rope_table(ws.cs, g, md.hd, md.rope_base, s);
+  PROFILED(ctx, SPECS_K_OTHER, s, launch_embed<T>(tokens, (const T*)m->w.embed, ws.x, g.M, md.d, md.V, ws.status, s);
+           launch_rope_table(ws.cs, g, md.hd, md.rope_base, s));
   for (int l = 0; l < d.n_layers; ++l) {
     const specs_layer_weights& L = m->layers[l];
     T* kb = (T*)ws.kblk + (size_t)l * R * kvd;
     T* vb = (T*)ws.vblk + (size_t)l * (R + 16 * C) * kvd;
     T* pK = pool_ptr<T>(p, d, l, 0);
     T* pV = pool_ptr<T>(p, d, l, 1);
-    launch_rmsnorm<T>(ws.x, L.g_attn, (T*)ws.a, g.M, md.d, md.eps, s);
-    gemm<T>((const T*)ws.a, (const T*)L.wqkv, ws.qkv, g.M, qd + 2 * kvd, md.d, EPI_STORE_F32, s);
-    launch_rope_split<T>(ws.qkv, ws.cs, (T*)ws.q, kb, vb, g, Lp, md, s);
-    attention<T>((const T*)ws.q, kb, vb, pK, pV, (T*)ws.attn, g, md, Lp, max_ctx, s);
+    PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(ws.x, L.g_attn, (T*)ws.a, g.M, md.d, md.eps, s));
+    PROFILED(ctx, SPECS_K_QKV, s,
+             gemm<T>((const T*)ws.a, (const T*)L.wqkv, ws.qkv, g.M, qd + 2 * kvd, md.d, EPI_STORE_F32, s));
+    PROFILED(ctx, SPECS_K_OTHER, s, launch_rope_split<T>(ws.qkv, ws.cs, (T*)ws.q, kb, vb, g, Lp, md, s));
+    PROFILED(ctx, SPECS_K_ATTENTION, s,
+             attention<T>((const T*)ws.q, kb, vb, pK, pV, (T*)ws.attn, g, md, Lp, max_ctx, s));
     if (commit_pages) launch_kv_commit<T>(kb, vb, pK, pV, g, md, Lp, nullptr, s);
-    gemm<T>((const T*)ws.attn, (const T*)L.wo, ws.x, g.M, md.d, qd, EPI_RESIDUAL_ADD, s);
-    launch_rmsnorm<T>(ws.x, L.g_ffn, (T*)ws.a, g.M, md.d, md.eps, s);
-    gate_up<T>((const T*)ws.a, (const T*)L.wgu, ws.gu, (T*)ws.act, g.M, md.F, md.d, s);
-    gemm<T>((const T*)ws.act, (const T*)L.wd, ws.x, g.M, md.d, md.F, EPI_RESIDUAL_ADD, s);
+    PROFILED(ctx, SPECS_K_OPROJ, s,
+             gemm<T>((const T*)ws.attn, (const T*)L.wo, ws.x, g.M, md.d, qd, EPI_RESIDUAL_ADD, s));
+    PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(ws.x, L.g_ffn, (T*)ws.a, g.M, md.d, md.eps, s));
+    PROFILED(ctx, SPECS_K_GATE_UP, s,
+             gate_up<T>((const T*)ws.a, (const T*)L.wgu, ws.gu, (T*)ws.act, g.M, md.F, md.d, s));
+    PROFILED(ctx, SPECS_K_DOWN, s,
+             gemm<T>((const T*)ws.act, (const T*)L.wd, ws.x, g.M, md.d, md.F, EPI_RESIDUAL_ADD, s));
   }
 }
 
@@ -309,14 +370,19 @@ static int score_impl(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
   int max_ctx = 0;
   for (int b = 0; b < p->B; ++b) max_ctx = p->lens[b] > max_ctx ? p->lens[b] : max_ctx;
   hipStream_t s = ctx->stream;
-  run_trunk<T>(m, p, ws, g, cand, max_ctx, false, R, C, s);
+  run_trunk<T>(ctx, m, p, ws, g, cand, max_ctx, false, R, C, s);
   if (d.head == SPECS_HEAD_LM) {
-    launch_rmsnorm_shifted<T>(ws.x, p->h_last, m->w.g_final, (T*)ws.a, g, d.d_model, d.rms_eps, s);
-    int tiles = lmhead_partials<T>((const T*)ws.a, (const T*)m->w.head, cand, ws.part_max, ws.part_sum, ws.zt, g.M,
-                                   d.vocab, d.d_model, s);
-    launch_lmhead_merge(ws.part_max, ws.part_sum, ws.zt, tiles, tok_logp, ws.tokl, out, g, s);
+    int tiles = 0;
+    PROFILED(ctx, SPECS_K_OTHER, s,
+             launch_rmsnorm_shifted<T>(ws.x, p->h_last, m->w.g_final, (T*)ws.a, g, d.d_model, d.rms_eps, s));
+    PROFILED(ctx, SPECS_K_LMHEAD, s,
+             tiles = lmhead_partials<T>((const T*)ws.a, (const T*)m->w.head, cand, ws.part_max, ws.part_sum, ws.zt,
+                                        g.M, d.vocab, d.d_model, s));
+    PROFILED(ctx, SPECS_K_OTHER, s,
+             launch_lmhead_merge(ws.part_max, ws.part_sum, ws.zt, tiles, tok_logp, ws.tokl, out, g, s));
   } else {
-    launch_prm_head<T>(ws.x, m->w.g_final, (const T*)m->w.head, out, g, d.d_model, d.rms_eps, s);
+    PROFILED(ctx, SPECS_K_OTHER, s,
+             launch_prm_head<T>(ws.x, m->w.g_final, (const T*)m->w.head, out, g, d.d_model, d.rms_eps, s));
   }
   HIP_TRY(hipGetLastError());
   ctx->last_model = m;
@@ -359,7 +425,7 @@ static int prefill_impl(specs_ctx* ctx, const specs_model* m, specs_prefix* p, c
       BatchGeom g;
       g.B = 1; g.n = 1; g.L = rows; g.M = rows; g.b0 = b; g.len_override = c0;
       g.lens = p->lens_dev; g.page_table = p->page_table; g.max_pages = p->max_pages; g.page_tokens = p->page_tokens;
-      run_trunk<T>(m, p, ws, g, tokens + off + c0, c0, true, R, 1, s);
+      run_trunk<T>(ctx, m, p, ws, g, tokens + off + c0, c0, true, R, 1, s);
       if (c0 + rows == len) launch_copy_rows(ws.x, p->h_last, g, d.d_model, nullptr, s);
     }
     off += len;

@@ -37,11 +37,13 @@ struct GemmArgs {
   float* zt;             // ME_LMHEAD: [M]
 };
 
-// One direct-to-LDS load instruction: span p (8 wavefronts x 1 KiB = 64 rows of 128 bytes) of an operand tile.
+// One direct-to-LDS load instruction: the workgroup's NW wavefronts write NW consecutive 1 KiB spans
+// (8 rows of 128 bytes each) of an operand tile.
+template <int NW>
 __device__ __forceinline__ void load_span_async(const bf16_t* __restrict__ G, int row0, int rows_total, int K, int k0,
                                                 char* lds_tile, int p) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  int span = p * 8 + wave;                   // 1 KiB of LDS = 8 rows, written by one wavefront
+  int span = p * NW + wave;                  // 1 KiB of LDS = 8 rows, written by one wavefront
   int q = span * 64 + lane;
   int row = q >> 3, slot = q & 7;
   int chunk = slot ^ ((row >> 1) & 7);
@@ -55,11 +57,11 @@ __device__ __forceinline__ bf16x8 lds_frag(const char* tile, int row, int chunk)
   return *(const bf16x8*)(tile + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
 }
 
-template <int BM, int EPI>
-__global__ void __launch_bounds__(512) gemm_mfma_kernel(GemmArgs a) {
+template <int BM, int EPI, int NWN>
+__global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   constexpr int BN = 256;
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
-  constexpr int WM = BM / 2, TM = WM / 32, TN = 2;
+  constexpr int NW = 2 * NWN;                         // wavefronts: 2 along M x NWN along N
+  constexpr int WM = BM / 2, TM = WM / 32, WN = BN / NWN, TN = WN / 32;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   // id -> (m_tile, n_tile): ids congruent mod 8 share an XCD; consecutive ids there walk the M-tiles of one N-tile
@@ -71,7 +73,7 @@ __global__ void __launch_bounds__(512) gemm_mfma_kernel(GemmArgs a) {
   const int m0 = m_tile * BM, n0 = n_tile * BN;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm = wave >> 2, wn = wave & 3;
+  const int wm = wave / NWN, wn = wave % NWN;
   const int lrow = lane & 31, lhalf = lane >> 5;
 
   floatx16 acc[TM][TN];
@@ -83,12 +85,19 @@ __global__ void __launch_bounds__(512) gemm_mfma_kernel(GemmArgs a) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int KT = a.K / 64;
-  auto read_frags = [&](const char* As, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
-    const char* Bs = As + A_BYTES;
+  // LDS ring of five slots; a slot holds one operand tile (A: BM x 64, W: 256 x 64). K-tile t uses slot 2t for
+  // W and slot 2t+1 for A (mod 5), so besides the two slots being multiplied three are in flight: the weights,
+  // which stream from HBM, are requested two K-tiles ahead, the activations one and a half.
+  constexpr int SLOT = 256 * 128;
+  auto wslot = [&](int t) { return smem + ((2 * t) % 5) * SLOT; };
+  auto aslot = [&](int t) { return smem + ((2 * t + 1) % 5) * SLOT; };
+  auto read_frags = [&](int t, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
+    const char* As = aslot(t);
+    const char* Bs = wslot(t);
 #pragma unroll
     for (int i = 0; i < TM; ++i) af[i] = lds_frag(As, wm * WM + i * 32 + lrow, ks * 2 + lhalf);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) bfr[j] = lds_frag(Bs, wn * 64 + j * 32 + lrow, ks * 2 + lhalf);
+    for (int j = 0; j < TN; ++j) bfr[j] = lds_frag(Bs, wn * WN + j * 32 + lrow, ks * 2 + lhalf);
   };
   auto mma = [&](const bf16x8 (&af)[TM], const bf16x8 (&bfr)[TN]) {
 #pragma unroll
@@ -97,15 +106,20 @@ __global__ void __launch_bounds__(512) gemm_mfma_kernel(GemmArgs a) {
       for (int j = 0; j < TN; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
   };
-  constexpr int LA = BM / 64, LB = BN / 64, LPT = LA + LB;   // direct-to-LDS loads per thread per K-tile
-  // load instruction i (0 .. LPT-1) of K-tile t into ring buffer `buf`
-  auto issue = [&](int i, int t, char* buf) {
-    if (i < LA) load_span_async(a.A, m0, a.M, a.K, t * 64, buf, i);
-    else load_span_async(a.W, n0, a.N, a.K, t * 64, buf + A_BYTES, i - LA);
+  constexpr int LA = BM / (8 * NW), LB = BN / (8 * NW);   // direct-to-LDS loads per thread per operand tile
+  auto issue_w = [&](int t) {
+    const int src = t < KT ? t : KT - 1;              // past the end: a redundant load into the free slot, never consumed
+#pragma unroll
+    for (int i = 0; i < LB; ++i) load_span_async<NW>(a.W, n0, a.N, a.K, src * 64, wslot(t), i);
+  };
+  auto issue_a = [&](int t) {
+    const int src = t < KT ? t : KT - 1;
+#pragma unroll
+    for (int i = 0; i < LA; ++i) load_span_async<NW>(a.A, m0, a.M, a.K, src * 64, aslot(t), i);
   };
   // One k-step of the software pipeline: two MFMAs of the current group go first, then the LDS reads of the
-  // next group (and, in the first k-step, the next K-tile's global loads) are issued, then the rest of the
-  // MFMAs. Nothing in the group waits on those reads.
+  // next group (and, after the barrier, the global loads that refill the two freed slots) are issued, then the
+  // rest of the MFMAs. Nothing in the group waits on those reads.
 #define PIPE_STEP_ORDER(NLOADS)                                        \
   __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                   \
   __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);             \
@@ -113,42 +127,38 @@ __global__ void __launch_bounds__(512) gemm_mfma_kernel(GemmArgs a) {
   __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - 2, 0);         \
   __builtin_amdgcn_sched_barrier(0)
 
-  constexpr int L0 = LPT, L1 = 0, L2 = 0;
-
-#pragma unroll
-  for (int i = 0; i < LPT; ++i) issue(i, 0, smem);
-  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+  issue_w(0); issue_a(0); issue_w(1); issue_a(1); issue_w(2);
+  // K-tile 0 has landed when only the three younger slots (W1, A1, W2) are still in flight
+  if (2 * LB + LA == 12) asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
+  else if (2 * LB + LA == 10) asm volatile("s_waitcnt vmcnt(10)\n\ts_barrier" ::: "memory");
+  else if (2 * LB + LA == 24) asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
+  else { static_assert(2 * LB + LA == 12 || 2 * LB + LA == 10 || 2 * LB + LA == 24 || 2 * LB + LA == 20, "");
+         asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory"); }
   bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
-  read_frags(smem, 0, a0, b0);
+  read_frags(0, 0, a0, b0);
   for (int kt = 0; kt < KT; ++kt) {
-    const char* cur = smem + (kt & 1) * STAGE;
-    char* nxt = smem + ((kt + 1) & 1) * STAGE;
-    // The loop body is branch-free so that each k-step stays one scheduling region: on the last K-tile the
-    // "next" tile is the last one again (a redundant reload into the free buffer, never consumed).
-    const int tn = kt + 1 < KT ? kt + 1 : KT - 1;
-    // every wavefront is past the barrier that ended K-tile kt-1, so its buffer (nxt) is free
-    read_frags(cur, 1, a1, b1);
-#pragma unroll
-    for (int i = 0; i < L0; ++i) issue(i, tn, nxt);
+    // The loop body is branch-free so that each k-step stays one scheduling region.
+    read_frags(kt, 1, a1, b1);
     mma(a0, b0);
-    PIPE_STEP_ORDER(L0);
-    read_frags(cur, 2, a0, b0);
-#pragma unroll
-    for (int i = L0; i < L0 + L1; ++i) issue(i, tn, nxt);
-    mma(a1, b1);
-    PIPE_STEP_ORDER(L1);
-    read_frags(cur, 3, a1, b1);
-#pragma unroll
-    for (int i = L0 + L1; i < LPT; ++i) issue(i, tn, nxt);
-    mma(a0, b0);
-    PIPE_STEP_ORDER(L2);
-    // publish K-tile kt+1: own loads landed, own reads of K-tile kt complete, then meet the other wavefronts
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    read_frags(nxt, 0, a0, b0);
+    PIPE_STEP_ORDER(0);
+    read_frags(kt, 2, a0, b0);
     mma(a1, b1);
     PIPE_STEP_ORDER(0);
+    read_frags(kt, 3, a1, b1);
+    mma(a0, b0);
+    PIPE_STEP_ORDER(0);
+    // Publish K-tile kt+1 (only W of K-tile kt+2 may still be in flight) and retire K-tile kt: own reads of it
+    // are complete, and after the barrier so are everybody's, so its two slots are refilled at once.
+    if (LB == 4) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    issue_a(kt + 2);
+    issue_w(kt + 3);
+    read_frags(kt + 1 < KT ? kt + 1 : kt, 0, a0, b0);
+    mma(a1, b1);
+    PIPE_STEP_ORDER(LA + LB);
   }
 #undef PIPE_STEP_ORDER
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // accumulator element r of lane: row 8*(r/4) + 4*lhalf + r%4, column lrow of the 32x32 tile
   if (EPI == ME_STORE || EPI == ME_RESIDUAL) {
@@ -156,7 +166,7 @@ __global__ void __launch_bounds__(512) gemm_mfma_kernel(GemmArgs a) {
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        int col = n0 + wn * 64 + j * 32 + lrow;
+        int col = n0 + wn * WN + j * 32 + lrow;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           int row = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
@@ -169,20 +179,23 @@ __global__ void __launch_bounds__(512) gemm_mfma_kernel(GemmArgs a) {
       }
   } else if (EPI == ME_SWIGLU) {
     const int F = a.N >> 1;
-    int fcol = ((n0 + wn * 64) >> 1) + lrow;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int jp = 0; jp < TN / 2; ++jp) {              // accumulator pair (2jp, 2jp+1) = gate, up of 32 units
+      int fcol = ((n0 + wn * WN + jp * 64) >> 1) + lrow;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        int row = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-        float g = acc[i][0][r], u = acc[i][1][r];
-        float v = g / (1.0f + expf(-g)) * u;
-        if (row < a.M && fcol < F) a.act[(size_t)row * F + fcol] = (bf16_t)v;
-      }
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          int row = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+          float g = acc[i][2 * jp][r], u = acc[i][2 * jp + 1][r];
+          float v = g * __frcp_rn(1.0f + __expf(-g)) * u;
+          if (row < a.M && fcol < F) a.act[(size_t)row * F + fcol] = (bf16_t)v;
+        }
+    }
   } else {  // ME_LMHEAD
     __syncthreads();                                   // every wavefront is done with the operand tiles
-    float* red_max = (float*)smem;                     // [BM][4]
-    float* red_sum = red_max + BM * 4;
+    float* red_max = (float*)smem;                     // [BM][NWN]
+    float* red_sum = red_max + BM * NWN;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -193,7 +206,7 @@ __global__ void __launch_bounds__(512) gemm_mfma_kernel(GemmArgs a) {
         float mx = -INFINITY;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          int col = n0 + wn * 64 + j * 32 + lrow;
+          int col = n0 + wn * WN + j * 32 + lrow;
           if (col < a.N) mx = fmaxf(mx, acc[i][j][r]);
           if (col == target) a.zt[row] = acc[i][j][r];
         }
@@ -202,25 +215,27 @@ __global__ void __launch_bounds__(512) gemm_mfma_kernel(GemmArgs a) {
         float sm = 0.f;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          int col = n0 + wn * 64 + j * 32 + lrow;
+          int col = n0 + wn * WN + j * 32 + lrow;
           if (col < a.N) sm += expf(acc[i][j][r] - mx);
         }
 #pragma unroll
         for (int o = 16; o > 0; o >>= 1) sm += __shfl_xor(sm, o, 64);
         if (lrow == 0) {
-          red_max[lr * 4 + wn] = mx;
-          red_sum[lr * 4 + wn] = sm;
+          red_max[lr * NWN + wn] = mx;
+          red_sum[lr * NWN + wn] = sm;
         }
       }
     __syncthreads();
-    for (int lr = threadIdx.x; lr < BM; lr += 512) {
+    for (int lr = threadIdx.x; lr < BM; lr += 64 * NW) {
       int row = m0 + lr;
       if (row < a.M) {
-        float mx = fmaxf(fmaxf(red_max[lr * 4], red_max[lr * 4 + 1]), fmaxf(red_max[lr * 4 + 2], red_max[lr * 4 + 3]));
+        float mx = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NWN; ++w) mx = fmaxf(mx, red_max[lr * NWN + w]);
         float sm = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w)
-          if (red_max[lr * 4 + w] > -INFINITY) sm += red_sum[lr * 4 + w] * expf(red_max[lr * 4 + w] - mx);
+        for (int w = 0; w < NWN; ++w)
+          if (red_max[lr * NWN + w] > -INFINITY) sm += red_sum[lr * NWN + w] * expf(red_max[lr * NWN + w] - mx);
         a.part_max[(size_t)row * a.n_tiles + n_tile] = mx;
         a.part_sum[(size_t)row * a.n_tiles + n_tile] = sm;
       }
@@ -228,16 +243,17 @@ __global__ void __launch_bounds__(512) gemm_mfma_kernel(GemmArgs a) {
   }
 }
 
-template <int BM, int EPI>
+template <int BM, int EPI, int NWN>
 static void launch_variant(const GemmArgs& a, hipStream_t s) {
-  constexpr int smem = 2 * (BM * 128 + 256 * 128);
+  constexpr int smem = 5 * 256 * 128;
   static bool configured = false;
   if (!configured) {
-    (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, EPI, NWN>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              smem);
     configured = true;
   }
   int groups = (a.n_tiles + 7) / 8;
-  gemm_mfma_kernel<BM, EPI><<<dim3(groups * 8 * a.m_tiles), 512, smem, s>>>(a);
+  gemm_mfma_kernel<BM, EPI, NWN><<<dim3(groups * 8 * a.m_tiles), 128 * NWN, smem, s>>>(a);
 }
 
 int mfma_lmhead_tiles(int V) { return (V + 255) / 256; }
@@ -251,12 +267,12 @@ bool launch_gemm_mfma(int epi, const bf16_t* A, const bf16_t* W, int M, int N, i
   a.A = A; a.W = W; a.M = M; a.N = N; a.K = K; a.C = C; a.act = act; a.tok = tok;
   a.part_max = part_max; a.part_sum = part_sum; a.zt = zt;
   a.n_tiles = (N + 255) / 256;
-  // 128-row tiles when 256-row tiles would leave most of the 256 CUs idle
-  bool small = ((M + 255) / 256) * a.n_tiles < 200 || M <= 128;
+  // 128-row tiles when twice as many workgroups still fit the 256 CUs in one round
+  bool small = ((M + 255) / 256) * a.n_tiles <= 128 || M <= 128;
   a.m_tiles = small ? (M + 127) / 128 : (M + 255) / 256;
-#define DISPATCH(E)                                   \
-  if (small) launch_variant<128, E>(a, s);            \
-  else launch_variant<256, E>(a, s);
+#define DISPATCH(E)                                                       \
+  if (small) launch_variant<128, E, 4>(a, s);                             \
+  else launch_variant<256, E, 4>(a, s);
   switch (epi) {
     case ME_STORE: DISPATCH(ME_STORE); break;
     case ME_RESIDUAL: DISPATCH(ME_RESIDUAL); break;

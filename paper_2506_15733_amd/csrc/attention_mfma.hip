@@ -45,7 +45,7 @@ __device__ __forceinline__ int k_swizzle(int row, int chunk) {
 }
 
 template <int HD, int QT>
-__global__ void __launch_bounds__(256) attention_mfma_kernel(AttnArgs a) {
+__global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(AttnArgs a) {
   constexpr int KROW = HD * 2;              // bytes per key row
   constexpr int KCH = HD / 8;               // 16-byte chunks per key row
   constexpr int K_BYTES = 64 * KROW;        // 64 keys
@@ -191,40 +191,45 @@ __global__ void __launch_bounds__(256) attention_mfma_kernel(AttnArgs a) {
 #pragma unroll
     for (int u = 0; u < QT; ++u) {
       const bool need_mask = is_block || (key_base + 64 > P);
-      const int limit = is_block ? tq[u] + 1 : P;      // keys < limit are visible
+      if (need_mask) {
+        const int limit = is_block ? tq[u] + 1 : P;      // keys < limit are visible
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            int key = key_base + hf * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
+            s[u][hf][r] = key < limit ? s[u][hf][r] : -INFINITY;
+          }
+      }
       float mx = -INFINITY;
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = s[u][hf][r] * a.scale_log2e;
-          if (need_mask) {
-            int key = key_base + hf * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
-            v = key < limit ? v : -INFINITY;
-          }
-          s[u][hf][r] = v;
-          mx = fmaxf(mx, v);
-        }
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[u][hf][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      float m_new = fmaxf(m_run[u], mx);
-      float alpha, m_use;
-      if (m_new == -INFINITY) { alpha = 1.f; m_use = 0.f; }   // nothing visible yet: p = exp2(-inf) = 0
-      else { alpha = exp2f(m_run[u] - m_new); m_use = m_new; }
+      // running maximum in the log2 domain: scores are scaled by scale*log2(e) > 0 inside the exponent's FMA
+      const float m_new = fmaxf(m_run[u], mx * a.scale_log2e);
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;   // nothing visible yet: every p below is exp2(-inf) = 0
+      // rescale the accumulators only when some row's maximum moved (rare after the first tiles)
+      if (__any(m_new > m_run[u])) {
+        const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run[u] - m_new);
+        l_run[u] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < NI; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[u][dt][r] *= alpha;
+      }
       m_run[u] = m_new;
       float psum = 0.f;
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float p = exp2f(s[u][hf][r] - m_use);
+          float p = __builtin_amdgcn_exp2f(fmaf(s[u][hf][r], a.scale_log2e, -m_use));
           psum += p;
           pf[u][hf * 2 + (r >> 3)][r & 7] = (bf16_t)p;
         }
-      l_run[u] = l_run[u] * alpha + psum;
-#pragma unroll
-      for (int dt = 0; dt < NI; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[u][dt][r] *= alpha;
+      l_run[u] += psum;
     }
 
     // O^T += V^T P^T : K-step = one 16-key group (page) pg, this lane supplies keys 8*lh .. 8*lh+7 of it
@@ -281,9 +286,9 @@ bool launch_attention_mfma(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT,
   a.Hq = md.Hq; a.Hkv = md.Hkv; a.Lp = Lp;
   a.scale_log2e = 1.4426950408889634f / sqrtf((float)md.hd);
   int rows = g.L * (md.Hq / md.Hkv);
-  // 256-row workgroups when they waste no more padding than 128-row ones
+  // 256-row workgroups only when they waste less padding than 128-row ones (the latter run two per CU)
   int t1 = (rows + 127) / 128, t2 = (rows + 255) / 256;
-  bool big = t2 * 256 <= t1 * 128;
+  bool big = t2 * 256 < t1 * 128;
   a.q_tiles = big ? t2 : t1;
   a.total_wg = g.B * md.Hkv * g.n * a.q_tiles;
   a.wg_per_xcd = (a.total_wg + 7) / 8;

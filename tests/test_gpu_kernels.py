@@ -35,7 +35,8 @@ def close(got, want, rel):
     return err
 
 
-LINEAR_SHAPES = [(45, 100, 64), (256, 256, 64), (300, 1152, 128), (130, 257, 192), (2048, 4608, 3584),
+LINEAR_SHAPES = [(45, 100, 64), (256, 256, 64), (300, 1152, 128), (130, 257, 192), (300, 1152, 256), (130, 257, 320),
+                 (77, 2100, 448), (2048, 4608, 3584),
                  (1024, 1536, 8960), (256, 1024, 2816), (2048, 3584, 18944)]
 
 
@@ -66,7 +67,7 @@ def test_linear_f32(ctx):
     close(out.cpu().numpy().astype(np.float64), oracle.linear(a, w), 2e-6)
 
 
-@pytest.mark.parametrize("M,F,K", [(45, 96, 64), (300, 160, 128), (256, 2816, 1024), (2048, 18944, 3584)])
+@pytest.mark.parametrize("M,F,K", [(45, 96, 64), (300, 160, 128), (300, 1120, 256), (256, 2816, 1024), (2048, 18944, 3584)])
 def test_gate_up_bf16(ctx, M, F, K):
     from paper_2506_15733_amd import binding as B
     from paper_2506_15733_amd.synthetic import pack_gate_up
@@ -87,7 +88,8 @@ def test_gate_up_bf16(ctx, M, F, K):
     assert np.all(np.abs(got - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-4 * rms)
 
 
-@pytest.mark.parametrize("M,V,K", [(45, 301, 64), (100, 1000, 128), (256, 32768, 1024), (512, 152064, 3584)])
+@pytest.mark.parametrize("M,V,K", [(45, 301, 64), (100, 1000, 128), (300, 5000, 256), (256, 32768, 1024), (512, 152064, 3584),
+                                   (300, 151936, 896)])
 def test_lmhead_logprob_bf16(ctx, M, V, K):
     from paper_2506_15733_amd import binding as B
     a, ta = draw(f"la{M}.{K}", (M, K))

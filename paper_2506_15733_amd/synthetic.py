@@ -41,6 +41,9 @@ class DeviceModel:
         nbytes = B.specs_workspace_bytes(self.cdesc, max_rows, max_blocks)
         assert nbytes > 0
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        # the block may still be written by queued work of the allocating stream: order the context's stream after it
+        stream.wait_stream(torch.cuda.current_stream())
+        self.workspace.record_stream(stream)
         self.ctx = B.specs_ctx_create(torch.device(device).index or 0, stream.cuda_stream, self.workspace)
         self.model = B.specs_model_create(self.ctx, self.cdesc, self.embed, self.head, self.g_final, self.layers)
 
@@ -74,16 +77,21 @@ class ScoringStep:
 
     ROLES = ("target", "draft", "prm")
 
-    def __init__(self, wl: W.Workload, device="cuda:0", extra_tokens=0, prefill_rows=2048):
+    def __init__(self, wl: W.Workload, device="cuda:0", extra_tokens=0, prefill_rows=2048, concurrent=True):
+        """concurrent: each role gets its own context on its own stream (default priority), so that the three
+        independent passes overlap where one of them leaves CUs idle (the paper runs target and PRM scoring
+        concurrently and pays for the slower of the two); SubSample joins them on the caller's stream."""
         self.wl, self.device = wl, device
         torch.cuda.set_device(device)
         self.stream = torch.cuda.current_stream()
+        self.concurrent = concurrent
+        self.role_streams = {r: (torch.cuda.Stream(device=device) if concurrent else self.stream) for r in self.ROLES}
         lens = wl.prefix_lens()
         rows = max(wl.B * wl.n * wl.L, min(int(lens.max()), prefill_rows))
         table, num_pages = wl.page_table(extra_tokens)
         self.models, self.prefixes = {}, {}
         for role, desc in wl.models().items():
-            self.models[role] = DeviceModel(desc, device, self.stream, rows, wl.B * wl.n, wl.seed)
+            self.models[role] = DeviceModel(desc, device, self.role_streams[role], rows, wl.B * wl.n, wl.seed)
             self.prefixes[role] = DevicePrefix(self.models[role], lens, table, num_pages, wl.page_tokens)
         self.cand = torch.from_numpy(wl.candidates()).to(device)
         self.prefix_tokens = torch.from_numpy(np.concatenate(wl.prefix_tokens()).astype(np.int32)).to(device)
@@ -93,10 +101,25 @@ class ScoringStep:
         self.tok = {r: f(wl.B, wl.n, wl.L) for r in ("target", "draft")}
         self.idx = torch.zeros((wl.B, len(wl.betas)), dtype=torch.int32, device=device)
         self.max_reward = f(wl.B)
+        # SubSample runs on the caller's stream after the three passes have joined it
+        self.sel_ws = torch.zeros(4096, dtype=torch.uint8, device=device)
+        self.sel_ctx = B.specs_ctx_create(torch.device(device).index or 0, self.stream.cuda_stream, self.sel_ws)
+
+    def _fork(self):
+        if self.concurrent:
+            for r in self.ROLES:
+                self.role_streams[r].wait_stream(self.stream)
+
+    def _join(self):
+        if self.concurrent:
+            for r in self.ROLES:
+                self.stream.wait_stream(self.role_streams[r])
 
     def prefill(self):
+        self._fork()
         for r in self.ROLES:
             B.specs_prefill(self.models[r].ctx, self.models[r].model, self.prefixes[r].handle, self.prefix_tokens)
+        self._join()
 
     def score(self, role, cand=None, out=None, tok=None):
         dm = self.models[role]
@@ -105,13 +128,17 @@ class ScoringStep:
                              (self.tok.get(role) if tok is None else tok))
 
     def enqueue_step(self):
+        self._fork()
         for r in self.ROLES:
             self.score(r)
-        B.specs_subsample(self.models["target"].ctx, self.out["target"], self.out["draft"], self.out["prm"],
+        self._join()
+        B.specs_subsample(self.sel_ctx, self.out["target"], self.out["draft"], self.out["prm"],
                           self.wl.betas, self.u, self.idx, None, self.max_reward)
 
     def status(self):
-        return {r: B.specs_ctx_status(self.models[r].ctx) for r in self.ROLES}
+        st = {r: B.specs_ctx_status(self.models[r].ctx) for r in self.ROLES}
+        st["subsample"] = B.specs_ctx_status(self.sel_ctx)
+        return st
 
     def score_and_select(self):
         self.enqueue_step()
@@ -126,6 +153,7 @@ class ScoringStep:
         return res
 
     def close(self):
+        B.specs_ctx_destroy(self.sel_ctx)
         for r in self.ROLES:
             self.prefixes[r].close()
             self.models[r].close()

@@ -185,6 +185,7 @@ def test_candidates_are_independent_and_permutable():
     perm = np.array([2, 0, 1])
     c2 = torch.from_numpy(np.ascontiguousarray(cand[:, perm])).to("cuda:0")
     out = torch.zeros_like(step.out["target"])
+    torch.cuda.synchronize()
     step.score("target", cand=c2, out=out, tok=torch.zeros_like(step.tok["target"]))
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy(), res["target"][:, perm])

@@ -292,3 +292,49 @@ def test_c5_batched_beams_paged_ragged_prefixes():
     for k in ("target", "draft", "prm", "idx"):
         assert np.array_equal(res[k], res2[k]), k
     step.close()
+
+
+@pytest.mark.parametrize("P,n,L,hq,hkv,hd", [
+    (1, 1, 1, 2, 2, 64),          # shortest possible trace, one candidate, one token
+    (17, 2, 3, 4, 4, 64),         # no grouping (Hq = Hkv), prefix inside one partial key tile
+    (64, 3, 65, 2, 1, 128),       # prefix exactly one key tile, block one token longer than a key tile
+    (200, 2, 130, 4, 2, 64),      # block spanning three key tiles and two 128-row query tiles per head group
+])
+def test_degenerate_and_boundary_shapes_bf16(P, n, L, hq, hkv, hd):
+    d = hq * hd
+    t = ModelDesc("target", 1, d, hq, hkv, hd, 128, 300, "bf16", "lm")
+    dr = ModelDesc("draft", 1, d, hq, hkv, hd, 64, 300, "bf16", "lm")
+    pr = ModelDesc("prm", 1, d, hq, hkv, hd, 128, 300, "bf16", "prm")
+    wl = Workload("edge", t, dr, pr, B=1, n=n, L=L, prefix_len=P, betas=(1.0,), token_dist="uniform", page_tokens=16,
+                  seed=21, u_seed=22)
+    step, res = run_step(wl)
+    want = oracle_step(wl)
+    noise = bf16_sensitivity(wl, want)
+    compare(res, want, "bf16", noise)
+    check_selection(wl, res, TOL_BF16, TOL_BF16, want)
+    step.close()
+
+
+def test_invalid_arguments_are_rejected():
+    from paper_2506_15733_amd import synthetic, binding as B
+    wl = ragged_workload("f32")
+    step = synthetic.ScoringStep(wl, concurrent=False)
+    step.prefill()
+    dm, pf = step.models["target"], step.prefixes["target"]
+    big = torch.zeros((wl.B, 64, 64), dtype=torch.int32, device="cuda:0")      # more rows than the workspace was sized for
+    with pytest.raises(B.SpecsError) as e:
+        B.specs_score_blocks(dm.ctx, dm.model, pf.handle, big, torch.zeros((wl.B, 64), device="cuda:0"))
+    assert e.value.code == 7                                                    # SPECS_EWORKSPACE
+    with pytest.raises(B.SpecsError) as e:                                      # a PRM pass has no per-token output
+        B.specs_score_blocks(step.models["prm"].ctx, step.models["prm"].model, step.prefixes["prm"].handle, step.cand,
+                             step.out["prm"], step.tok["target"])
+    assert e.value.code == 1
+    with pytest.raises(B.SpecsError) as e:                                      # prefix handle of another model
+        B.specs_score_blocks(dm.ctx, dm.model, step.prefixes["prm"].handle, step.cand, step.out["target"])
+    assert e.value.code == 1
+    with pytest.raises(B.SpecsError) as e:                                      # commit without a preceding scoring call
+        B.specs_commit_block(step.models["draft"].ctx, step.models["draft"].model, step.prefixes["draft"].handle, [0, 0, 0])
+    assert e.value.code == 1
+    res = step.score_and_select()                                               # the handles are still usable
+    assert np.all(np.isfinite(res["target"]))
+    step.close()

@@ -79,7 +79,7 @@ def kernel_bench(args):
     dev = "cuda:0"
     M = wl.B * wl.n * wl.L
     qd, kvd = d.n_q_heads * d.head_dim, d.n_kv_heads * d.head_dim
-    ws = torch.zeros(2 << 30, dtype=torch.uint8, device=dev)
+    ws = torch.zeros(3 << 30, dtype=torch.uint8, device=dev)
     ctx = B.specs_ctx_create(0, torch.cuda.current_stream().cuda_stream, ws)
     bf = lambda *s: (torch.randn(s, device=dev) * 0.5).to(torch.bfloat16)
     wt = lambda n, k: device_tensor(d, 0, f"bench/{n}.{k}", (n, k), dev)

@@ -29,6 +29,7 @@ struct GemmArgs {
   const bf16_t* W;
   int M, N, K;
   int m_tiles, n_tiles;
+  int m_blocks;          // ceil(m_tiles / 8)
   float* C;              // ME_STORE / ME_RESIDUAL: [M, N]
   bf16_t* act;           // ME_SWIGLU: [M, N/2]
   const int32_t* tok;    // ME_LMHEAD: target token per row
@@ -64,12 +65,15 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   constexpr int WM = BM / 2, TM = WM / 32, WN = BN / NWN, TN = WN / 32;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-  // id -> (m_tile, n_tile): ids congruent mod 8 share an XCD; consecutive ids there walk the M-tiles of one N-tile
+  // id -> (m_tile, n_tile): ids congruent mod 8 share an XCD. An XCD owns the N-tiles n = 8j + xcd; the 32
+  // workgroups that run on it at one time form a block of 8 M-tiles x 4 of its N-tiles, so that every A panel
+  // is fetched into that XCD's L2 once per 4 users and every W tile once per 8 users.
   const int id = blockIdx.x;
   const int xcd = id & 7, seq = id >> 3;
-  const int m_tile = seq % a.m_tiles;
-  const int n_tile = (seq / a.m_tiles) * 8 + xcd;
-  if (n_tile >= a.n_tiles) return;
+  const int blk = seq >> 5, within = seq & 31;
+  const int m_tile = (blk % a.m_blocks) * 8 + (within & 7);
+  const int n_tile = ((blk / a.m_blocks) * 4 + (within >> 3)) * 8 + xcd;
+  if (n_tile >= a.n_tiles || m_tile >= a.m_tiles) return;
   const int m0 = m_tile * BM, n0 = n_tile * BN;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -252,8 +256,9 @@ static void launch_variant(const GemmArgs& a, hipStream_t s) {
                               smem);
     configured = true;
   }
-  int groups = (a.n_tiles + 7) / 8;
-  gemm_mfma_kernel<BM, EPI, NWN><<<dim3(groups * 8 * a.m_tiles), 128 * NWN, smem, s>>>(a);
+  int per_xcd = (a.n_tiles + 7) / 8;                 // N-tiles owned by one XCD
+  int blocks = a.m_blocks * ((per_xcd + 3) / 4);     // 8 x 4 blocks per XCD
+  gemm_mfma_kernel<BM, EPI, NWN><<<dim3(blocks * 32 * 8), 128 * NWN, smem, s>>>(a);
 }
 
 int mfma_lmhead_tiles(int V) { return (V + 255) / 256; }
@@ -270,6 +275,7 @@ bool launch_gemm_mfma(int epi, const bf16_t* A, const bf16_t* W, int M, int N, i
   // 128-row tiles when twice as many workgroups still fit the 256 CUs in one round
   bool small = ((M + 255) / 256) * a.n_tiles <= 128 || M <= 128;
   a.m_tiles = small ? (M + 127) / 128 : (M + 255) / 256;
+  a.m_blocks = (a.m_tiles + 7) / 8;
 #define DISPATCH(E)                                                       \
   if (small) launch_variant<128, E, 4>(a, s);                             \
   else launch_variant<256, E, 4>(a, s);

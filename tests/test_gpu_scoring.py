@@ -338,3 +338,32 @@ def test_invalid_arguments_are_rejected():
     res = step.score_and_select()                                               # the handles are still usable
     assert np.all(np.isfinite(res["target"]))
     step.close()
+
+
+def test_multi_step_loop_with_commit_and_switching_matches_oracle():
+    """Alg. 1 over H iterations on the GPU (score, SubSample, commit, switch test) against the same loop written
+    with the oracle: the chosen indices and the switching decisions must be identical."""
+    from paper_2506_15733_amd import synthetic
+    wl = ragged_workload("f32")
+    H, tau = 4, 0.5
+    step = synthetic.ScoringStep(wl, extra_tokens=H * wl.L)
+    step.prefill()
+    blocks = [W.rng.uniform_tokens(31, f"loop/{h}", wl.B * wl.n * wl.L, wl.token_vocab).reshape(wl.B, wl.n, wl.L)
+              for h in range(H)]
+    chosen, gen = synthetic.run_specs_loop(step, blocks, tau)
+    # the oracle's loop
+    traces = [p.copy() for p in wl.prefix_tokens()]
+    use_draft = np.zeros(wl.B, dtype=bool)
+    u_all = W.rng.uniform_f64(wl.u_seed, "loop/u", H * wl.B).reshape(H, wl.B)
+    for h in range(H):
+        sc = oracle_step(wl, cand=blocks[h], prefix_tokens=traces)
+        for b in range(wl.B):
+            lgen = sc["draft"][b] if use_draft[b] else sc["target"][b]
+            k = oracle.subsample(sc["target"][b], lgen, sc["prm"][b], wl.betas[0], float(u_all[h, b]))
+            assert gen[h, b] == use_draft[b]
+            assert chosen[h, b] == k, (h, b)
+            traces[b] = np.concatenate([traces[b], blocks[h][b, k]])
+        use_draft |= sc["prm"].max(axis=1) > tau
+    assert gen.any() and not gen.all()          # the run exercises both generators
+    assert step.prefixes["target"].lens_dev.cpu().tolist() == [len(t) for t in traces]
+    step.close()

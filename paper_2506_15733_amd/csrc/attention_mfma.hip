@@ -18,7 +18,9 @@
 // The A-rows of the S^T product are fed with keys in the order pi(i) (the two middle groups of
 // four swapped inside every 16) so that the eight accumulator values a lane holds for one MFMA
 // K-step of the second product are eight CONSECUTIVE keys: with V stored transposed
-// ([head_dim][16 tokens] per page) the matching A-operand is one 16-byte LDS read.
+// ([head_dim][16 tokens] per page) the matching A-operand is one 16-byte LDS read. In LDS the two 16-byte
+// halves of a V^T row are swapped for rows with bit 3 set, so that 16 consecutive lanes (rows 32 bytes apart,
+// same half) cover all 64 banks instead of every other 16-byte column.
 #include "common.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -128,8 +130,11 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
         __builtin_amdgcn_global_load_lds(GLB_PTR(ksrc + row * HD + chunk * 8), LDS_PTR(kdst + i * 1024), 16, 0, 0);
       }
 #pragma unroll
-      for (int i = 0; i < NI; ++i)
-        __builtin_amdgcn_global_load_lds(GLB_PTR(vsrc + (i * 64 + lane) * 8), LDS_PTR(vdst + i * 1024), 16, 0, 0);
+      for (int i = 0; i < NI; ++i) {
+        int qi = i * 64 + lane;
+        int d = qi >> 1, half = (qi & 1) ^ ((d >> 3) & 1);       // LDS chunk position qi&1 holds key half `half`
+        __builtin_amdgcn_global_load_lds(GLB_PTR(vsrc + d * 16 + half * 8), LDS_PTR(vdst + i * 1024), 16, 0, 0);
+      }
     } else {
       int key0 = (tile - n_ptiles) * 64 + wave * 16;
 #pragma unroll
@@ -146,7 +151,7 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
 #pragma unroll
       for (int i = 0; i < NI; ++i) {
         int qi = i * 64 + lane;
-        int d = qi >> 1, half = qi & 1;
+        int d = qi >> 1, half = (qi & 1) ^ ((d >> 3) & 1);
         int key = key0 + half * 8;
         key = key < a.Lp ? key : a.Lp - 8;
         __builtin_amdgcn_global_load_lds(GLB_PTR(vsrc + (size_t)d * a.Lp + key), LDS_PTR(vdst + i * 1024), 16, 0, 0);
@@ -175,16 +180,16 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
       for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[u][hf][r] = 0.f;
+    // K-step outer, key half inner: the two accumulator chains of a query tile alternate
 #pragma unroll
-    for (int hf = 0; hf < 2; ++hf) {
-      int row = hf * 32 + pi_row;
+    for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
+      for (int hf = 0; hf < 2; ++hf) {
+        int row = hf * 32 + pi_row;
         bf16x8 kf = *(const bf16x8*)(Ks + row * KROW + (k_swizzle<HD>(row, ks * 2 + lh) << 4));
 #pragma unroll
         for (int u = 0; u < QT; ++u) s[u][hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[u][ks], s[u][hf], 0, 0, 0);
       }
-    }
 
     // accumulator value r of half hf in this lane is key  key_base + hf*32 + 16*(r/8) + 8*lh + r%8
     bf16x8 pf[QT][4];
@@ -237,7 +242,7 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
     for (int pg = 0; pg < 4; ++pg)
 #pragma unroll
       for (int dt = 0; dt < NI; ++dt) {
-        bf16x8 vf = *(const bf16x8*)(Vs + pg * HD * 32 + (dt * 32 + lq) * 32 + lh * 16);
+        bf16x8 vf = *(const bf16x8*)(Vs + pg * HD * 32 + (dt * 32 + lq) * 32 + ((lh ^ ((lq >> 3) & 1)) << 4));
 #pragma unroll
         for (int u = 0; u < QT; ++u) o[u][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u][pg], o[u][dt], 0, 0, 0);
       }

@@ -95,6 +95,15 @@ void launch_subsample(const float* lt, const float* lg, const float* r, const ui
 
 // bf16 MFMA GEMM family (gemm_mfma.hip). Returns false if the shape is not supported.
 enum { MFMA_STORE = 0, MFMA_RESIDUAL = 1, MFMA_SWIGLU = 2, MFMA_LMHEAD = 3 };
+// ksplit > 1 (MFMA_STORE only): C is [ksplit][M][N], one partial product per K slice; bm = 128, 256 or 0 (auto).
 bool launch_gemm_mfma(int epi, const bf16_t* A, const bf16_t* W, int M, int N, int K, float* C, bf16_t* act,
-                      const int32_t* tok, float* part_max, float* part_sum, float* zt, hipStream_t s);
+                      const int32_t* tok, float* part_max, float* part_sum, float* zt, int ksplit, int bm,
+                      hipStream_t s);
+// tile height and number of K slices for a product whose consumer sums up to max_split partial products
+void mfma_gemm_plan(int M, int N, int K, int max_split, int* bm_out, int* split_out);
+// x[M,d] (+)= sum of `parts` partial products P[parts][M,d]; init != 0 overwrites x instead of adding to it.
+// With gain != nullptr also out = RMSNorm(x) * gain (the operand of the next projection).
+template <typename T>
+void launch_add_partials_rmsnorm(float* x, const float* P, int parts, int init, const float* gain, T* out, int M, int d,
+                                 float eps, hipStream_t s);
 int mfma_lmhead_tiles(int V);

@@ -48,6 +48,69 @@ __device__ __forceinline__ void rmsnorm_row(const float* __restrict__ xr, const 
   for (int c = threadIdx.x; c < d; c += 256) yr[c] = from_f32<T>(xr[c] * inv * gain[c]);
 }
 
+// Vector form for rows of d <= 4096 floats, d % 4 == 0, 16-byte aligned: the row stays in registers (at most four
+// float4 per thread) between the sum of squares and the scaled store. parts > 0: x (+)= sum of the K-split
+// partial products P[parts][M][d] first (summed in slice order, then added to x), and x is written back.
+template <typename T>
+__device__ __forceinline__ void store4(T* p, float4 v);
+template <>
+__device__ __forceinline__ void store4<float>(float* p, float4 v) { *(float4*)p = v; }
+template <>
+__device__ __forceinline__ void store4<bf16_t>(bf16_t* p, float4 v) {
+  typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+  bf16x4 o = {(__bf16)v.x, (__bf16)v.y, (__bf16)v.z, (__bf16)v.w};
+  *(bf16x4*)p = o;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) norm_rows_vec_kernel(float* __restrict__ x, const float* __restrict__ P,
+                                                            int parts, int init, const float* __restrict__ gain,
+                                                            T* __restrict__ out, size_t Md, int d, float eps) {
+  __shared__ float red[4];
+  const size_t m = blockIdx.x;
+  const int nv = d >> 2;
+  float4* xr = (float4*)(x + m * d);
+  float4 v[4];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int c = threadIdx.x + i * 256;
+    if (c < nv) {
+      if (parts > 0) {
+        float4 acc = ((const float4*)(P + m * d))[c];
+        for (int sidx = 1; sidx < parts; ++sidx) {
+          float4 q = ((const float4*)(P + sidx * Md + m * d))[c];
+          acc.x += q.x; acc.y += q.y; acc.z += q.z; acc.w += q.w;
+        }
+        if (!init) {
+          float4 o = xr[c];
+          acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+        }
+        v[i] = acc;
+        xr[c] = acc;
+      } else {
+        v[i] = xr[c];
+      }
+      ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+    }
+  }
+  if (gain == nullptr) return;
+  ss = block_sum_256(ss, red);
+  float inv = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int c = threadIdx.x + i * 256;
+    if (c < nv) {
+      float4 gn = ((const float4*)gain)[c];
+      float4 y = {v[i].x * inv * gn.x, v[i].y * inv * gn.y, v[i].z * inv * gn.z, v[i].w * inv * gn.w};
+      store4<T>(out + m * d + 4 * c, y);
+    }
+  }
+}
+static inline bool vec_rows_ok(int d, const void* a, const void* b, const void* c, const void* e) {
+  return d % 4 == 0 && d <= 4096 && (((uintptr_t)a | (uintptr_t)b | (uintptr_t)c | (uintptr_t)e) & 15) == 0;
+}
+
 template <typename T>
 __global__ void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain, T* __restrict__ out, int d,
                                float eps) {
@@ -57,10 +120,50 @@ __global__ void rmsnorm_kernel(const float* __restrict__ x, const float* __restr
 }
 template <typename T>
 void launch_rmsnorm(const float* x, const float* gain, T* out, int M, int d, float eps, hipStream_t s) {
-  rmsnorm_kernel<T><<<M, 256, 0, s>>>(x, gain, out, d, eps);
+  if (vec_rows_ok(d, x, gain, out, nullptr))
+    norm_rows_vec_kernel<T><<<M, 256, 0, s>>>((float*)x, nullptr, 0, 0, gain, out, 0, d, eps);
+  else
+    rmsnorm_kernel<T><<<M, 256, 0, s>>>(x, gain, out, d, eps);
 }
 template void launch_rmsnorm<float>(const float*, const float*, float*, int, int, float, hipStream_t);
 template void launch_rmsnorm<bf16_t>(const float*, const float*, bf16_t*, int, int, float, hipStream_t);
+
+// Consumer of a K-split projection: x (+)= sum of the partial products, then (optionally) the RMSNorm of the
+// updated row, which the next projection reads. The partials are summed first, in slice order, and then added
+// to the residual stream, so the result does not depend on how the workgroups were scheduled.
+template <typename T>
+__global__ void add_partials_rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ P, int parts, int init,
+                                            const float* __restrict__ gain, T* __restrict__ out, size_t Md, int d,
+                                            float eps) {
+  __shared__ float red[4];
+  size_t m = blockIdx.x;
+  float* xr = x + m * d;
+  const float* pr = P + m * d;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    float acc = pr[c];
+    for (int sidx = 1; sidx < parts; ++sidx) acc += pr[sidx * Md + c];
+    float v = init ? acc : xr[c] + acc;
+    xr[c] = v;
+    ss += v * v;
+  }
+  if (gain == nullptr) return;
+  ss = block_sum_256(ss, red);
+  float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int c = threadIdx.x; c < d; c += 256) out[m * d + c] = from_f32<T>(xr[c] * inv * gain[c]);
+}
+template <typename T>
+void launch_add_partials_rmsnorm(float* x, const float* P, int parts, int init, const float* gain, T* out, int M, int d,
+                                 float eps, hipStream_t s) {
+  if (vec_rows_ok(d, x, P, gain, out))
+    norm_rows_vec_kernel<T><<<M, 256, 0, s>>>(x, P, parts, init, gain, out, (size_t)M * d, d, eps);
+  else
+    add_partials_rmsnorm_kernel<T><<<M, 256, 0, s>>>(x, P, parts, init, gain, out, (size_t)M * d, d, eps);
+}
+template void launch_add_partials_rmsnorm<float>(float*, const float*, int, int, const float*, float*, int, int, float,
+                                                 hipStream_t);
+template void launch_add_partials_rmsnorm<bf16_t>(float*, const float*, int, int, const float*, bf16_t*, int, int,
+                                                  float, hipStream_t);
 
 // Operand of the vocabulary head: the hidden state that PRECEDES each scored token.
 template <typename T>

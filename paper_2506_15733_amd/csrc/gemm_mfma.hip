@@ -36,6 +36,7 @@ struct GemmArgs {
   float* part_max;       // ME_LMHEAD: [M, n_tiles]
   float* part_sum;
   float* zt;             // ME_LMHEAD: [M]
+  int ksplit;            // ME_STORE only: gridDim.y slices of K, slice s writes its partial product to C + s*M*N
 };
 
 // One direct-to-LDS load instruction: the workgroup's NW wavefronts write NW consecutive 1 KiB spans
@@ -88,7 +89,9 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int KT = a.K / 64;
+  // K-tiles [kt0, kt0 + KT) of this workgroup's K slice
+  const int kt0 = (int)((long)blockIdx.y * (a.K / 64) / a.ksplit);
+  const int KT = (int)((long)(blockIdx.y + 1) * (a.K / 64) / a.ksplit) - kt0;
   // LDS ring of five slots; a slot holds one operand tile (A: BM x 64, W: 256 x 64). K-tile t uses slot 2t for
   // W and slot 2t+1 for A (mod 5), so besides the two slots being multiplied three are in flight: the weights,
   // which stream from HBM, are requested two K-tiles ahead, the activations one and a half.
@@ -114,12 +117,12 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   auto issue_w = [&](int t) {
     const int src = t < KT ? t : KT - 1;              // past the end: a redundant load into the free slot, never consumed
 #pragma unroll
-    for (int i = 0; i < LB; ++i) load_span_async<NW>(a.W, n0, a.N, a.K, src * 64, wslot(t), i);
+    for (int i = 0; i < LB; ++i) load_span_async<NW>(a.W, n0, a.N, a.K, (kt0 + src) * 64, wslot(t), i);
   };
   auto issue_a = [&](int t) {
     const int src = t < KT ? t : KT - 1;
 #pragma unroll
-    for (int i = 0; i < LA; ++i) load_span_async<NW>(a.A, m0, a.M, a.K, src * 64, aslot(t), i);
+    for (int i = 0; i < LA; ++i) load_span_async<NW>(a.A, m0, a.M, a.K, (kt0 + src) * 64, aslot(t), i);
   };
   // One k-step of the software pipeline: two MFMAs of the current group go first, then the LDS reads of the
   // next group (and, after the barrier, the global loads that refill the two freed slots) are issued, then the
@@ -166,6 +169,7 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
 
   // accumulator element r of lane: row 8*(r/4) + 4*lhalf + r%4, column lrow of the 32x32 tile
   if (EPI == ME_STORE || EPI == ME_RESIDUAL) {
+    float* __restrict__ Cs = a.C + (size_t)blockIdx.y * a.M * a.N;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -176,8 +180,8 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
           int row = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
           if (row < a.M && col < a.N) {
             size_t o = (size_t)row * a.N + col;
-            if (EPI == ME_RESIDUAL) a.C[o] += acc[i][j][r];
-            else a.C[o] = acc[i][j][r];
+            if (EPI == ME_RESIDUAL) Cs[o] += acc[i][j][r];
+            else Cs[o] = acc[i][j][r];
           }
         }
       }
@@ -258,22 +262,46 @@ static void launch_variant(const GemmArgs& a, hipStream_t s) {
   }
   int per_xcd = (a.n_tiles + 7) / 8;                 // N-tiles owned by one XCD
   int blocks = a.m_blocks * ((per_xcd + 3) / 4);     // 8 x 4 blocks per XCD
-  gemm_mfma_kernel<BM, EPI, NWN><<<dim3(blocks * 32 * 8), 128 * NWN, smem, s>>>(a);
+  gemm_mfma_kernel<BM, EPI, NWN><<<dim3(blocks * 32 * 8, a.ksplit), 128 * NWN, smem, s>>>(a);
 }
 
 int mfma_lmhead_tiles(int V) { return (V + 255) / 256; }
 
+// Tile height and K-split for an M x N x K product whose consumer can sum partial products. Times in
+// microseconds from measurements on the 256-CU part: one 64-deep k-step of a resident workgroup costs c(BM),
+// workgroups run in rounds of 256, a launch has a fixed cost, and every extra partial costs one more
+// M x N float write here plus one read in the consumer.
+void mfma_gemm_plan(int M, int N, int K, int max_split, int* bm_out, int* split_out) {
+  const int KT = K / 64, n_tiles = (N + 255) / 256;
+  double best = 1e30;
+  *bm_out = 256; *split_out = 1;
+  for (int bm = M <= 128 ? 128 : 256; bm >= 128; bm >>= 1) {
+    long tiles = (long)((M + bm - 1) / bm) * n_tiles;
+    double c = bm == 256 ? 1.55 : 1.08;
+    for (int sp = 1; sp <= max_split && sp <= 8 && sp * 4 <= KT + 3; ++sp) {
+      long rounds = (tiles * sp + 255) / 256;
+      double t = (double)rounds * ((KT + sp - 1) / sp) * c + 8.0 + (2 * sp - 2) * (double)M * N * 4.0 / 4e6;
+      if (t < best - 1e-9) { best = t; *bm_out = bm; *split_out = sp; }
+    }
+  }
+}
+
 // Returns false when the shape is not one this kernel takes (the caller then uses the SIMT kernel).
+// ksplit > 1 (ME_STORE only): C is [ksplit][M][N] and receives the partial products of the K slices.
+// bm: tile height 128 or 256, 0 = chosen here.
 bool launch_gemm_mfma(int epi, const bf16_t* A, const bf16_t* W, int M, int N, int K, float* C, bf16_t* act,
-                      const int32_t* tok, float* part_max, float* part_sum, float* zt, hipStream_t s) {
+                      const int32_t* tok, float* part_max, float* part_sum, float* zt, int ksplit, int bm,
+                      hipStream_t s) {
   if (K % 64 != 0 || M <= 0 || N <= 0) return false;
   if (epi == ME_SWIGLU && (N % 64 != 0)) return false;
+  if (ksplit < 1 || (ksplit > 1 && (epi != ME_STORE || ksplit > K / 64))) return false;
+  if (bm != 0 && bm != 128 && bm != 256) return false;
   GemmArgs a;
   a.A = A; a.W = W; a.M = M; a.N = N; a.K = K; a.C = C; a.act = act; a.tok = tok;
-  a.part_max = part_max; a.part_sum = part_sum; a.zt = zt;
+  a.part_max = part_max; a.part_sum = part_sum; a.zt = zt; a.ksplit = ksplit;
   a.n_tiles = (N + 255) / 256;
   // 128-row tiles when twice as many workgroups still fit the 256 CUs in one round
-  bool small = ((M + 255) / 256) * a.n_tiles <= 128 || M <= 128;
+  bool small = bm ? bm == 128 : ((M + 255) / 256) * a.n_tiles <= 128 || M <= 128;
   a.m_tiles = small ? (M + 127) / 128 : (M + 255) / 256;
   a.m_blocks = (a.m_tiles + 7) / 8;
 #define DISPATCH(E)                                                       \

@@ -281,8 +281,29 @@ static void gemm(const T* A, const T* W, float* C, int M, int N, int K, GemmEpil
 template <>
 void gemm<bf16_t>(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmEpilogue epi, hipStream_t s) {
   int e = epi == EPI_RESIDUAL_ADD ? MFMA_RESIDUAL : MFMA_STORE;
-  if (!launch_gemm_mfma(e, A, W, M, N, K, C, nullptr, nullptr, nullptr, nullptr, nullptr, s))
+  if (!launch_gemm_mfma(e, A, W, M, N, K, C, nullptr, nullptr, nullptr, nullptr, nullptr, 1, 0, s))
     launch_gemm_simple<bf16_t>(A, W, C, M, N, K, epi, s);
+}
+
+// K-split form of x += A W^T for the residual projections: when the plan says that slicing K fills the CUs
+// better, writes the partial products to `part` (room for max_split of them) and returns their number;
+// the caller's next normalisation kernel sums them into x. Returns 0 when the product was added to x directly.
+template <typename T>
+static int gemm_residual_split(const T* A, const T* W, float* x, float* part, int max_split, int M, int N, int K,
+                               hipStream_t s) {
+  gemm<T>(A, W, x, M, N, K, EPI_RESIDUAL_ADD, s);
+  return 0;
+}
+template <>
+int gemm_residual_split<bf16_t>(const bf16_t* A, const bf16_t* W, float* x, float* part, int max_split, int M, int N,
+                                int K, hipStream_t s) {
+  int bm = 0, split = 1;
+  if (K % 64 == 0 && max_split > 1) mfma_gemm_plan(M, N, K, max_split, &bm, &split);
+  if (split > 1 &&
+      launch_gemm_mfma(MFMA_STORE, A, W, M, N, K, part, nullptr, nullptr, nullptr, nullptr, nullptr, split, bm, s))
+    return split;
+  gemm<bf16_t>(A, W, x, M, N, K, EPI_RESIDUAL_ADD, s);
+  return 0;
 }
 
 // act[M,F] = silu(A Wg^T) * (A Wu^T) with Wgu interleaved by 32 rows
@@ -293,7 +314,7 @@ static void gate_up(const T* A, const T* Wgu, float* gu, T* act, int M, int F, i
 }
 template <>
 void gate_up<bf16_t>(const bf16_t* A, const bf16_t* Wgu, float* gu, bf16_t* act, int M, int F, int K, hipStream_t s) {
-  if (launch_gemm_mfma(MFMA_SWIGLU, A, Wgu, M, 2 * F, K, nullptr, act, nullptr, nullptr, nullptr, nullptr, s)) return;
+  if (launch_gemm_mfma(MFMA_SWIGLU, A, Wgu, M, 2 * F, K, nullptr, act, nullptr, nullptr, nullptr, nullptr, 1, 0, s)) return;
   launch_gemm_simple<bf16_t>(A, Wgu, gu, M, 2 * F, K, EPI_STORE_F32, s);
   launch_silu_mul<bf16_t>(gu, act, M, F, s);
 }
@@ -309,7 +330,7 @@ static int lmhead_partials(const T* A, const T* W, const int32_t* tok, float* pm
 template <>
 int lmhead_partials<bf16_t>(const bf16_t* A, const bf16_t* W, const int32_t* tok, float* pm, float* ps, float* zt, int M,
                             int V, int K, hipStream_t s) {
-  if (launch_gemm_mfma(MFMA_LMHEAD, A, W, M, V, K, nullptr, nullptr, tok, pm, ps, zt, s)) return mfma_lmhead_tiles(V);
+  if (launch_gemm_mfma(MFMA_LMHEAD, A, W, M, V, K, nullptr, nullptr, tok, pm, ps, zt, 1, 0, s)) return mfma_lmhead_tiles(V);
   int tiles = 0;
   launch_lmhead_partials_simple<bf16_t>(A, W, tok, pm, ps, zt, M, V, K, &tiles, s);
   return tiles;
@@ -333,26 +354,43 @@ static void run_trunk(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
   int qd = md.Hq * md.hd, kvd = md.Hkv * md.hd;
   PROFILED(ctx, SPECS_K_OTHER, s, launch_embed<T>(tokens, (const T*)m->w.embed, ws.x, g.M, md.d, md.V, ws.status, s);
            launch_rope_table(ws.cs, g, md.hd, md.rope_base, s));
+  // ws.gu ([R, 2F] floats) is free while the residual projections run (the fused gate/up kernel never writes
+  // it, the unfused path has consumed it by then), so it holds their K-split partial products.
+  const int max_split = (int)((2 * (size_t)md.F) / (size_t)md.d);
+  bool normed = false;                                   // ws.a already holds RMSNorm(x) * g_attn of this layer
   for (int l = 0; l < d.n_layers; ++l) {
     const specs_layer_weights& L = m->layers[l];
     T* kb = (T*)ws.kblk + (size_t)l * R * kvd;
     T* vb = (T*)ws.vblk + (size_t)l * (R + 16 * C) * kvd;
     T* pK = pool_ptr<T>(p, d, l, 0);
     T* pV = pool_ptr<T>(p, d, l, 1);
-    PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(ws.x, L.g_attn, (T*)ws.a, g.M, md.d, md.eps, s));
+    if (!normed) PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(ws.x, L.g_attn, (T*)ws.a, g.M, md.d, md.eps, s));
     PROFILED(ctx, SPECS_K_QKV, s,
              gemm<T>((const T*)ws.a, (const T*)L.wqkv, ws.qkv, g.M, qd + 2 * kvd, md.d, EPI_STORE_F32, s));
     PROFILED(ctx, SPECS_K_OTHER, s, launch_rope_split<T>(ws.qkv, ws.cs, (T*)ws.q, kb, vb, g, Lp, md, s));
     PROFILED(ctx, SPECS_K_ATTENTION, s,
              attention<T>((const T*)ws.q, kb, vb, pK, pV, (T*)ws.attn, g, md, Lp, max_ctx, s));
     if (commit_pages) launch_kv_commit<T>(kb, vb, pK, pV, g, md, Lp, nullptr, s);
+    int parts = 0;
     PROFILED(ctx, SPECS_K_OPROJ, s,
-             gemm<T>((const T*)ws.attn, (const T*)L.wo, ws.x, g.M, md.d, qd, EPI_RESIDUAL_ADD, s));
-    PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(ws.x, L.g_ffn, (T*)ws.a, g.M, md.d, md.eps, s));
+             parts = gemm_residual_split<T>((const T*)ws.attn, (const T*)L.wo, ws.x, ws.gu, max_split, g.M, md.d, qd, s));
+    if (parts)
+      PROFILED(ctx, SPECS_K_OTHER, s,
+               launch_add_partials_rmsnorm<T>(ws.x, ws.gu, parts, 0, L.g_ffn, (T*)ws.a, g.M, md.d, md.eps, s));
+    else
+      PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(ws.x, L.g_ffn, (T*)ws.a, g.M, md.d, md.eps, s));
     PROFILED(ctx, SPECS_K_GATE_UP, s,
              gate_up<T>((const T*)ws.a, (const T*)L.wgu, ws.gu, (T*)ws.act, g.M, md.F, md.d, s));
     PROFILED(ctx, SPECS_K_DOWN, s,
-             gemm<T>((const T*)ws.act, (const T*)L.wd, ws.x, g.M, md.d, md.F, EPI_RESIDUAL_ADD, s));
+             parts = gemm_residual_split<T>((const T*)ws.act, (const T*)L.wd, ws.x, ws.gu, max_split, g.M, md.d, md.F, s));
+    normed = false;
+    if (parts) {
+      // the sum of the partials is folded into the next layer's first normalisation (none after the last layer)
+      const float* next_gain = l + 1 < d.n_layers ? m->layers[l + 1].g_attn : nullptr;
+      PROFILED(ctx, SPECS_K_OTHER, s,
+               launch_add_partials_rmsnorm<T>(ws.x, ws.gu, parts, 0, next_gain, (T*)ws.a, g.M, md.d, md.eps, s));
+      normed = next_gain != nullptr;
+    }
   }
 }
 
@@ -507,8 +545,23 @@ extern "C" int specs_op_linear(specs_ctx* ctx, int32_t dtype, const void* A, con
   if (dtype != SPECS_F32 && dtype != SPECS_BF16) return SPECS_EINVAL;
   HIP_TRY(hipSetDevice(ctx->device));
   GemmEpilogue e = accumulate ? EPI_RESIDUAL_ADD : EPI_STORE_F32;
-  if (dtype == SPECS_BF16) gemm<bf16_t>((const bf16_t*)A, (const bf16_t*)W, C, M, N, K, e, ctx->stream);
-  else gemm<float>((const float*)A, (const float*)W, C, M, N, K, e, ctx->stream);
+  if (dtype == SPECS_BF16) {
+    // same K-split decision as inside the scoring pass, as far as the workspace has room for the partial products
+    size_t per = (size_t)M * N * sizeof(float);
+    size_t room = ctx->workspace_bytes > 256 ? (ctx->workspace_bytes - 256) / per : 0;
+    int bm = 0, split = 1;
+    if (K % 64 == 0 && room > 1) mfma_gemm_plan(M, N, K, room > 8 ? 8 : (int)room, &bm, &split);
+    float* part = (float*)(ctx->workspace + 256);
+    if (split > 1 && launch_gemm_mfma(MFMA_STORE, (const bf16_t*)A, (const bf16_t*)W, M, N, K, part, nullptr, nullptr,
+                                      nullptr, nullptr, nullptr, split, bm, ctx->stream)) {
+      launch_add_partials_rmsnorm<bf16_t>(C, part, split, accumulate ? 0 : 1, nullptr, nullptr, M, N, 0.f, ctx->stream);
+      ctx->last_model = nullptr;                         // the workspace no longer holds a scored block
+    } else {
+      gemm<bf16_t>((const bf16_t*)A, (const bf16_t*)W, C, M, N, K, e, ctx->stream);
+    }
+  } else {
+    gemm<float>((const float*)A, (const float*)W, C, M, N, K, e, ctx->stream);
+  }
   HIP_TRY(hipGetLastError());
   return SPECS_OK;
 }

@@ -59,6 +59,15 @@ __device__ __forceinline__ bf16x8 lds_frag(const char* tile, int row, int chunk)
   return *(const bf16x8*)(tile + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
 }
 
+// Value of lane (l ^ 1), (l ^ 2), and of the mirrored lane within 8 or 16 lanes, as data-parallel-primitive moves
+// of the vector ALU (no LDS crossbar traffic). After the two quad steps all four lanes of a quad agree, so the
+// mirrored reads bring in exactly the other half of the 8- (16-) lane group.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
+
 template <int BM, int EPI, int NWN>
 __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   constexpr int BN = 256;
@@ -202,37 +211,72 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
     }
   } else {  // ME_LMHEAD
     __syncthreads();                                   // every wavefront is done with the operand tiles
-    float* red_max = (float*)smem;                     // [BM][NWN]
+    int* tgt = (int*)smem;                             // [BM] target token of each row of the tile
+    float* red_max = (float*)(smem + BM * 4);          // [BM][NWN]
     float* red_sum = red_max + BM * NWN;
+    for (int t = threadIdx.x; t < BM; t += 64 * NW) tgt[t] = m0 + t < a.M ? a.tok[m0 + t] : -1;
+    __syncthreads();
+    // the lane's rows come in runs of four (r & 3): one 16-byte LDS read per run, all before the reductions
+    int4 tg[TM][4];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
+      for (int rq = 0; rq < 4; ++rq) tg[i][rq] = *(const int4*)(tgt + wm * WM + i * 32 + 8 * rq + 4 * lhalf);
+    // The 16 rows of one accumulator are reduced across the 32 lanes in lockstep, stage by stage, so that the
+    // 16 cross-lane exchanges of a stage are independent and their latencies overlap.
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      float mx[16], sm[16];
+#pragma unroll
       for (int r = 0; r < 16; ++r) {
-        int lr = wm * WM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-        int row = m0 + lr;
-        int target = row < a.M ? a.tok[row] : -1;
-        float mx = -INFINITY;
+        const int4 t4 = tg[i][r >> 2];
+        int target = (r & 3) == 0 ? t4.x : (r & 3) == 1 ? t4.y : (r & 3) == 2 ? t4.z : t4.w;
+        mx[r] = -INFINITY;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           int col = n0 + wn * WN + j * 32 + lrow;
-          if (col < a.N) mx = fmaxf(mx, acc[i][j][r]);
-          if (col == target) a.zt[row] = acc[i][j][r];
-        }
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-        float sm = 0.f;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          int col = n0 + wn * WN + j * 32 + lrow;
-          if (col < a.N) sm += expf(acc[i][j][r] - mx);
-        }
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) sm += __shfl_xor(sm, o, 64);
-        if (lrow == 0) {
-          red_max[lr * NWN + wn] = mx;
-          red_sum[lr * NWN + wn] = sm;
+          if (col < a.N) mx[r] = fmaxf(mx[r], acc[i][j][r]);
+          if (col == target) a.zt[m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3)] = acc[i][j][r];
         }
       }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx[r] = fmaxf(mx[r], dpp_move<DPP_XOR1>(mx[r]));
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx[r] = fmaxf(mx[r], dpp_move<DPP_XOR2>(mx[r]));
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx[r] = fmaxf(mx[r], dpp_move<DPP_HALF_MIRROR>(mx[r]));
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx[r] = fmaxf(mx[r], dpp_move<DPP_MIRROR>(mx[r]));
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx[r] = fmaxf(mx[r], __shfl_xor(mx[r], 16, 64));
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        sm[r] = 0.f;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          int col = n0 + wn * WN + j * 32 + lrow;
+          if (col < a.N) sm[r] += __expf(acc[i][j][r] - mx[r]);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sm[r] += dpp_move<DPP_XOR1>(sm[r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sm[r] += dpp_move<DPP_XOR2>(sm[r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sm[r] += dpp_move<DPP_HALF_MIRROR>(sm[r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sm[r] += dpp_move<DPP_MIRROR>(sm[r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sm[r] += __shfl_xor(sm[r], 16, 64);
+      if (lrow == 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          int lr = wm * WM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+          red_max[lr * NWN + wn] = mx[r];
+          red_sum[lr * NWN + wn] = sm[r];
+        }
+      }
+    }
     __syncthreads();
     for (int lr = threadIdx.x; lr < BM; lr += 64 * NW) {
       int row = m0 + lr;

@@ -159,38 +159,62 @@ class ScoringStep:
             self.models[r].close()
 
 
-def run_specs_loop(step: ScoringStep, blocks, tau, beta_index=0, start_with_target=True):
+def run_specs_loop(step: ScoringStep, blocks, tau, beta_index=0, start_with_target=True, fast_path=True):
     """Alg. 1 with a synthetic generator: for each iteration h, blocks[h] is the [B, n, L] candidate set the
     generator proposed (token ids; generation itself is outside this path). Step II: score, SubSample, append the
     chosen block to the trace of all three models (specs_commit_block). Step III: per beam, once
     max_i r(Y_i|tr) > tau the generator switches from the target to the draft model, for good.
     While a beam's generator IS the target, pi_gen = pi_target and the score collapses to beta * r (Eq. 1),
     which is passed to SubSample as logp_gen := logp_target.
-    Returns the chosen indices [H, B] and the generator flags [H, B] (True = draft generated that iteration)."""
+    fast_path: in an iteration where EVERY beam's generator is the target, no log-likelihood enters the score, so
+    only the PRM scores the n candidates; target and draft then run over the one chosen block per beam (n = 1),
+    which is all their caches need.
+    Returns the chosen indices [H, B], the generator flags [H, B] (True = draft generated that iteration) and,
+    per iteration, whether the PRM-only path ran."""
     wl = step.wl
     use_draft = np.zeros(wl.B, dtype=bool) if start_with_target else np.ones(wl.B, dtype=bool)
-    chosen_all, gen_all = [], []
+    chosen_all, gen_all, fast_all = [], [], []
     u_all = W.rng.uniform_f64(wl.u_seed, "loop/u", len(blocks) * wl.B).reshape(len(blocks), wl.B)
     betas = (wl.betas[beta_index],)
     idx = torch.zeros((wl.B, 1), dtype=torch.int32, device=step.device)
+    zeros = torch.zeros((wl.B, wl.n), dtype=torch.float32, device=step.device)
+    out1 = {r: torch.zeros((wl.B, 1), dtype=torch.float32, device=step.device) for r in ("target", "draft")}
+    tok1 = {r: torch.zeros((wl.B, 1, wl.L), dtype=torch.float32, device=step.device) for r in ("target", "draft")}
+    beams = torch.arange(wl.B, device=step.device)
     for h, cand in enumerate(blocks):
         step.cand = torch.from_numpy(np.ascontiguousarray(cand.astype(np.int32))).to(step.device)
+        fast = fast_path and not use_draft.any()
+        u = torch.from_numpy(u_all[h:h + 1].T.copy()).to(step.device)
         step._fork()
-        for r in step.ROLES:
+        for r in (("prm",) if fast else step.ROLES):
             step.score(r)
         step._join()
-        # generator = target for beams that have not switched: the log-ratio term vanishes (argument selection only)
-        mask = torch.from_numpy(use_draft).to(step.device)[:, None]
-        lgen = torch.where(mask, step.out["draft"], step.out["target"])
-        u = torch.from_numpy(u_all[h:h + 1].T.copy()).to(step.device)
-        B.specs_subsample(step.sel_ctx, step.out["target"], lgen.contiguous(), step.out["prm"], betas, u, idx, None,
-                          step.max_reward)
+        if fast:
+            B.specs_subsample(step.sel_ctx, zeros, zeros, step.out["prm"], betas, u, idx, None, step.max_reward)
+        else:
+            # generator = target for beams that have not switched: the log-ratio term vanishes
+            mask = torch.from_numpy(use_draft).to(step.device)[:, None]
+            lgen = torch.where(mask, step.out["draft"], step.out["target"])
+            B.specs_subsample(step.sel_ctx, step.out["target"], lgen.contiguous(), step.out["prm"], betas, u, idx,
+                              None, step.max_reward)
         torch.cuda.synchronize()
         chosen = idx[:, 0].cpu().numpy()
         gen_all.append(use_draft.copy())
         chosen_all.append(chosen.copy())
-        for r in step.ROLES:
-            B.specs_commit_block(step.models[r].ctx, step.models[r].model, step.prefixes[r].handle, chosen.tolist())
+        fast_all.append(fast)
+        if fast:
+            picked = step.cand[beams, idx[:, 0].long()][:, None, :].contiguous()       # [B, 1, L]
+            step._fork()
+            for r in ("target", "draft"):
+                step.score(r, cand=picked, out=out1[r], tok=tok1[r])
+                B.specs_commit_block(step.models[r].ctx, step.models[r].model, step.prefixes[r].handle, [0] * wl.B)
+            B.specs_commit_block(step.models["prm"].ctx, step.models["prm"].model, step.prefixes["prm"].handle,
+                                 chosen.tolist())
+            step._join()
+        else:
+            for r in step.ROLES:
+                B.specs_commit_block(step.models[r].ctx, step.models[r].model, step.prefixes[r].handle,
+                                     chosen.tolist())
         use_draft |= step.max_reward.cpu().numpy() > tau
     torch.cuda.synchronize()
-    return np.array(chosen_all), np.array(gen_all)
+    return np.array(chosen_all), np.array(gen_all), np.array(fast_all)

@@ -340,9 +340,13 @@ def test_invalid_arguments_are_rejected():
     step.close()
 
 
-def test_multi_step_loop_with_commit_and_switching_matches_oracle():
+@pytest.mark.parametrize("fast_path", [False, True])
+def test_multi_step_loop_with_commit_and_switching_matches_oracle(fast_path):
     """Alg. 1 over H iterations on the GPU (score, SubSample, commit, switch test) against the same loop written
-    with the oracle: the chosen indices and the switching decisions must be identical."""
+    with the oracle: the chosen indices and the switching decisions must be identical. With fast_path the
+    iterations whose generator is the target for every beam score the candidates with the PRM alone (Eq. 1 with
+    pi_gen = pi_target) and extend the target and draft caches by the chosen block only; later iterations, scored
+    by all three models against those caches, must still agree with the oracle."""
     from paper_2506_15733_amd import synthetic
     wl = ragged_workload("f32")
     H, tau = 4, 0.5
@@ -350,8 +354,9 @@ def test_multi_step_loop_with_commit_and_switching_matches_oracle():
     step.prefill()
     blocks = [W.rng.uniform_tokens(31, f"loop/{h}", wl.B * wl.n * wl.L, wl.token_vocab).reshape(wl.B, wl.n, wl.L)
               for h in range(H)]
-    chosen, gen = synthetic.run_specs_loop(step, blocks, tau)
-    # the oracle's loop
+    chosen, gen, fast = synthetic.run_specs_loop(step, blocks, tau, fast_path=fast_path)
+    assert fast.any() == fast_path              # with it on, at least the first iteration is PRM-only
+    # the oracle's loop: always the full definition (all three models score all n blocks)
     traces = [p.copy() for p in wl.prefix_tokens()]
     use_draft = np.zeros(wl.B, dtype=bool)
     u_all = W.rng.uniform_f64(wl.u_seed, "loop/u", H * wl.B).reshape(H, wl.B)

@@ -8,3 +8,4 @@ from .rounding import round_bf16, operand
 from .transformer import (linear, gate_up, token_logprob, silu, log_softmax, rms_norm, rope, swiglu_ffn, attention, forward_sequences,
                           block_logprobs_full, reward_full, prefill, score_cached, PrefixCache)
 from .subsample import scores, selection_probs, subsample, subsample_batch
+from . import smc

@@ -79,3 +79,36 @@ def test_device_side_errors_are_reported_not_fatal(ctx):
     assert e.value.code == 4
     idx, _, st = run(ctx, z, z, z, (1.0,), np.array([[0.3]]))
     assert st == 0 and idx.tolist() == [[1]]                                   # the context is still usable
+
+
+def test_monte_carlo_marginal_matches_the_exact_smc_policy(ctx):
+    """Statistical check of the kernel as a sampler: 2^18 independent SMC trials on a four-response space (draws
+    from pi_gen and uniforms from the seeded generator, scores from the toy tables) selected by the GPU kernel;
+    the histogram of returned responses must match the exact induced policy (enumeration over count vectors in
+    oracle.smc) within five binomial standard deviations, for soft selection, and for hard best-of-n at beta = 1e4
+    with generator = target."""
+    import math
+    from oracle import smc
+    g = np.random.default_rng(11)
+    pt, pd, r = g.dirichlet(np.ones(4) * 2), g.dirichlet(np.ones(4) * 2), g.uniform(0, 1, 4)
+    N, trials = 8, 1 << 18
+    draws = np.minimum(np.searchsorted(np.cumsum(pd), W.rng.uniform_f64(7, "mc/draws", trials * N), side="right"), 3)
+    draws = draws.reshape(trials, N)
+    u = W.rng.uniform_f64(7, "mc/u", trials * 2).reshape(trials, 2)
+    lt, ld, rr = np.log(pt)[draws], np.log(pd)[draws], r[draws]
+    idx, _, st = run(ctx, lt, ld, rr, (2.0,), u[:, :1])
+    assert st == 0
+    picked = draws[np.arange(trials), idx[:, 0]]
+    exact = smc.smc_policy(pd.tolist(), smc.exponentiated_score(pt.tolist(), pd.tolist(), r.tolist(), 2.0), N)
+    for k in range(4):
+        sd = math.sqrt(exact[k] * (1 - exact[k]) / trials)
+        assert abs(np.mean(picked == k) - exact[k]) < 5 * sd, (k, np.mean(picked == k), exact[k])
+    # hard selection: generator = target (log-ratio zero), beta = 1e4 -> the draw with the largest reward
+    idx, _, st = run(ctx, ld, ld, rr, (1e4,), u[:, 1:])
+    assert st == 0
+    picked = draws[np.arange(trials), idx[:, 0]]
+    assert np.array_equal(rr[np.arange(trials), idx[:, 0]], rr.max(axis=1))
+    hard = smc.best_of_n_policy(pd.tolist(), r.tolist(), N)
+    for k in range(4):
+        sd = math.sqrt(max(hard[k] * (1 - hard[k]), 1e-9) / trials)
+        assert abs(np.mean(picked == k) - hard[k]) < 5 * sd, (k, np.mean(picked == k), hard[k])

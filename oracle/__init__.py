@@ -9,3 +9,4 @@ from .transformer import (linear, gate_up, token_logprob, silu, log_softmax, rms
                           block_logprobs_full, reward_full, prefill, score_cached, PrefixCache)
 from .subsample import scores, selection_probs, subsample, subsample_batch
 from . import smc
+from .generate import generate_blocks, sample_token

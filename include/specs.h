@@ -149,8 +149,23 @@ int specs_prefill(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const i
 int specs_score_blocks(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const int32_t* cand,
                        int32_t n, int32_t L, float* out, float* tok_logp);
 
-/* Appends candidate `chosen[b]` (host array [B]) of the LAST specs_score_blocks call made with this
- * model and prefix to the cache (Alg. 1 step II, tr <- (tr, Y)): copies its L keys/values into the
+/* Generation of the candidate blocks (Alg. 1, Step I): the model (LM head) draws n blocks of L tokens
+ * for every beam from pi(. | tr), token by token, each token by ancestral sampling from the full
+ * softmax at temperature 1: with c_k the running sum of exp(z_v - max z) over ids v <= k,
+ * y = min{k : c_k > u * c_limit}, the inverse distribution function in id order read at the caller's
+ * uniform u[b][i][t] (device, doubles in [0,1); SPECS_ERANGE on the status word otherwise).
+ * vocab_limit: 0, or the number of leading ids that may be drawn (ids >= vocab_limit get probability
+ * zero and the rest is renormalised; for models whose vocabulary is larger than that of the models
+ * that will score the blocks). Outputs (device): cand[B][n][L] the tokens, logp[B][n] =
+ * log pi(Y_i | tr), the block log-likelihood under the law the tokens were drawn from (it comes out of
+ * the same pass, so a generator need not be run again as a scorer), and, if tok_logp != NULL,
+ * tok_logp[B][n][L] its per-token terms. The prefix is not modified; the context is left as after
+ * specs_score_blocks(cand) with this model and prefix, so specs_commit_block may follow. */
+int specs_generate_blocks(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, int32_t n, int32_t L,
+                          int32_t vocab_limit, const double* u, int32_t* cand, float* logp, float* tok_logp);
+
+/* Appends candidate `chosen[b]` (host array [B]) of the LAST specs_score_blocks or specs_generate_blocks
+ * call made with this model and prefix to the cache (Alg. 1 step II, tr <- (tr, Y)): copies its L keys/values into the
  * pages, sets h_last to its last hidden state and advances lens (host copy inside the handle and
  * the device array). The page table must already cover lens + L tokens. */
 int specs_commit_block(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* chosen_host);

@@ -15,8 +15,9 @@ from .rounding import operand
 from .transformer import PrefixCache, forward_sequences, rms_norm, _f64
 
 
-def sample_token(z, u):
-    """(token id, log softmax(z)[token]) for one row of logits z and one uniform u."""
+def sample_token(z, u, with_interval=False):
+    """(token id, log softmax(z)[token]) for one row of logits z and one uniform u; with_interval adds the
+    interval [c_{k-1}/c_V, c_k/c_V) of uniforms that map to the token."""
     if not (0.0 <= u < 1.0):
         raise ValueError("u must lie in [0,1)")
     m = float(np.max(z))
@@ -26,23 +27,31 @@ def sample_token(z, u):
     k = int(np.searchsorted(c, thr, side="right"))        # first index with c_k > thr
     if k >= len(z):
         k = int(np.nonzero(w > 0)[0][-1])
-    return k, float(z[k]) - m - float(np.log(c[-1]))
+    lp = float(z[k]) - m - float(np.log(c[-1]))
+    if with_interval:
+        return k, lp, ((float(c[k - 1]) if k else 0.0) / float(c[-1]), float(c[k]) / float(c[-1]))
+    return k, lp
 
 
-def generate_blocks(desc, weights, cache: PrefixCache, n, L, u):
-    """u [n, L] uniforms. Returns (tokens [n, L] int64, token log-probs [n, L], block log-probs [n],
-    caches: per candidate the prefix cache extended by its block, whose h_last is the state at its last token)."""
+def generate_blocks(desc, weights, cache: PrefixCache, n, L, u, vocab_limit=None):
+    """u [n, L] uniforms; vocab_limit: only the first vocab_limit ids may be drawn (softmax restricted to them).
+    Returns (tokens [n, L] int64, token log-probs [n, L], block log-probs [n],
+    caches: per candidate the prefix cache extended by its block, whose h_last is the state at its last token,
+    bounds [n, L, 2]: the interval of uniforms that maps to each drawn token)."""
     u = np.asarray(u, dtype=np.float64).reshape(n, L)
     head = _f64(weights.head())
     gain = weights.gains()["final"]
     caches = [PrefixCache(cache.length, list(cache.K), list(cache.V), cache.h_last.copy()) for _ in range(n)]
     tokens = np.zeros((n, L), dtype=np.int64)
     logp = np.zeros((n, L))
+    bounds = np.zeros((n, L, 2))
     for t in range(L):
         H = np.stack([c.h_last for c in caches])
         z = operand(rms_norm(H, gain, desc.rms_eps), desc.dtype) @ head.T
+        if vocab_limit:
+            z = z[:, :vocab_limit]
         for i in range(n):
-            tokens[i, t], logp[i, t] = sample_token(z[i], float(u[i, t]))
+            tokens[i, t], logp[i, t], bounds[i, t] = sample_token(z[i], float(u[i, t]), with_interval=True)
         xs, kv = forward_sequences(desc, weights, [tokens[i:i + 1, t:t + 1] for i in range(n)], prefixes=caches,
                                    collect_kv=True)
         caches = [PrefixCache(c.length + 1,
@@ -50,4 +59,4 @@ def generate_blocks(desc, weights, cache: PrefixCache, n, L, u):
                               [np.concatenate([c.V[l], kv[i][l][1]], axis=0) for l in range(desc.n_layers)],
                               xs[i][0, -1, :].copy()) for i, c in enumerate(caches)]
     block = np.array([sum(float(v) for v in row) for row in logp])
-    return tokens, logp, block, caches
+    return tokens, logp, block, caches, bounds

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libspecs_hip.so")
 EXPORTED_SYMBOLS = [
     "specs_workspace_bytes", "specs_ctx_create", "specs_ctx_destroy", "specs_ctx_status", "specs_model_create",
     "specs_model_destroy", "specs_prefix_create", "specs_prefix_destroy", "specs_prefill", "specs_score_blocks",
-    "specs_commit_block", "specs_subsample", "specs_strerror",
+    "specs_commit_block", "specs_subsample", "specs_strerror", "specs_generate_blocks",
     "specs_op_linear", "specs_op_gate_up", "specs_op_lmhead_logprob", "specs_op_attention",
     "specs_ctx_profile", "specs_ctx_profile_read",
 ]
@@ -185,6 +185,16 @@ def specs_score_blocks(ctx, model, prefix, cand, out, tok_logp=None):
     _check(load_library().specs_score_blocks(ctx, model, prefix, _ptr(cand, torch.int32), n, L,
                                              _ptr(out, torch.float32), _ptr(tok_logp, torch.float32, True)),
            "specs_score_blocks")
+
+
+def specs_generate_blocks(ctx, model, prefix, u, cand, logp, tok_logp=None, vocab_limit=0):
+    """u [B, n, L] float64 uniforms; cand [B, n, L] int32 (out), logp [B, n] (out), tok_logp [B, n, L] (out) or None."""
+    import torch
+    B, n, L = cand.shape
+    assert tuple(u.shape) == (B, n, L) and tuple(logp.shape) == (B, n)
+    _check(load_library().specs_generate_blocks(ctx, model, prefix, n, L, int(vocab_limit), _ptr(u, torch.float64),
+                                                _ptr(cand, torch.int32), _ptr(logp, torch.float32),
+                                                _ptr(tok_logp, torch.float32, True)), "specs_generate_blocks")
 
 
 def specs_commit_block(ctx, model, prefix, chosen_host):

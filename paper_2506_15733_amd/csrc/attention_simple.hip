@@ -1,5 +1,6 @@
 // Straightforward shared-prefix attention: one wavefront per (row, query head). Serves the float
-// configuration and head sizes the MFMA kernel does not take. Three passes over the keys:
+// configuration, head sizes the MFMA kernel does not take, and launches that cover one in-block position of every
+// candidate (row m = candidate m / L at position t0 + m % L; its block keys are rows cand*Lk .. of kb). Three passes over the keys:
 // scores into LDS (+ max), un-normalised weights exp(s - max) (+ sum), weighted sum of V.
 #include "common.h"
 
@@ -11,7 +12,7 @@ __global__ void __launch_bounds__(64) attention_simple_kernel(const T* __restric
   extern __shared__ float sc[];                 // [ctx + t + 1] scores, then weights
   int m = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
   int nL = g.n * g.L;
-  int b = m / nL, t = m % g.L;
+  int b = m / nL, t = g.t0 + m % g.L;               // in-block position of this row
   int ctx = g.len_override >= 0 ? g.len_override : g.lens[g.b0 + b];
   int kvh = h / (Hq / Hkv);
   int nkeys = ctx + t + 1;
@@ -28,7 +29,7 @@ __global__ void __launch_bounds__(64) attention_simple_kernel(const T* __restric
       int page = pt[j / g.page_tokens], slot = j % g.page_tokens;
       kr = poolK + (((size_t)page * Hkv + kvh) * g.page_tokens + slot) * hd;
     } else {
-      kr = kb + ((size_t)(m - t + (j - ctx)) * Hkv + kvh) * hd;
+      kr = kb + (((size_t)(m / g.L) * g.Lk + (j - ctx)) * Hkv + kvh) * hd;
     }
     float dot = 0.f;
     for (int c = 0; c < hd; ++c) dot = fmaf(qs[c], to_f32<T>(kr[c]), dot);
@@ -68,7 +69,7 @@ __global__ void __launch_bounds__(64) attention_simple_kernel(const T* __restric
 template <typename T>
 void launch_attention_simple(const T* q, const T* kb, const T* vbT, const T* poolK, const T* poolV, T* out,
                              const BatchGeom& g, const ModelDims& md, int Lp, int max_ctx, hipStream_t s) {
-  size_t lds = (size_t)(max_ctx + g.L + md.hd) * sizeof(float);
+  size_t lds = (size_t)(max_ctx + g.Lk + md.hd) * sizeof(float);
   float scale = 1.0f / sqrtf((float)md.hd);
   (void)hipFuncSetAttribute((const void*)attention_simple_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   attention_simple_kernel<T><<<dim3(g.M, md.Hq), 64, lds, s>>>(q, kb, vbT, poolK, poolV, out, g, md.Hq, md.Hkv, md.hd,

@@ -33,6 +33,9 @@ struct BatchGeom {
   int M;                    // B*n*L
   int b0;                   // first beam of the prefix handle this launch covers (prefill: one beam at a time)
   int len_override;         // >= 0: context length used instead of lens[b] (prefill chunks)
+  int t0;                   // in-block position of a row's first token: 0 when a launch covers whole blocks,
+                            // t when it covers the single position t of every block (token-by-token generation)
+  int Lk;                   // block length of the block key/value buffers (= L unless t0 > 0 launches are in use)
   const int32_t* lens;      // device [B_total]
   const int32_t* page_table;// device [B_total][max_pages]
   int max_pages, page_tokens;
@@ -45,7 +48,8 @@ struct ModelDims {
 
 // ---- launchers implemented across the .hip files (all enqueue on `s`) ----
 template <typename T>
-void launch_embed(const int32_t* tok, const T* E, float* x, int M, int d, int V, int* status, hipStream_t s);
+void launch_embed(const int32_t* tok, int tok_stride, const T* E, float* x, int M, int d, int V, int* status,
+                  hipStream_t s);   // row m embeds tok[m * tok_stride]
 template <typename T>
 void launch_rmsnorm(const float* x, const float* gain, T* out, int M, int d, float eps, hipStream_t s);
 // lm_head operand: row (b,i,t) = norm(t == 0 ? h_last[b0+b] : x[row-1])
@@ -68,6 +72,16 @@ template <typename T>
 void launch_prm_head(const float* x, const float* gain, const T* w, float* out, const BatchGeom& g, int d, float eps,
                      hipStream_t s);
 void launch_copy_rows(const float* x, float* h_last, const BatchGeom& g, int d, const int32_t* chosen, hipStream_t s);
+// generation: xs[b*n + i] = h_last[b0 + b] (every candidate starts from the prefix's last hidden state)
+void launch_broadcast_hlast(const float* h_last, float* xs, const BatchGeom& g, int d, hipStream_t s);
+// generation: x[(c*L + L-1)] = xs[c] for every candidate c (the state at the last block token, where scoring leaves it)
+void launch_scatter_last_rows(const float* xs, float* x, int C, int L, int d, hipStream_t s);
+// block_out[c] = sum_t tok_logp[c][t] in index order, accumulated in double
+void launch_block_sum(const float* tok_logp, float* block_out, int L, int C, hipStream_t s);
+// Ancestral sampling of one token per row from softmax(logits[row, :limit]) by inverse CDF in id order from the
+// uniform u[row*L + t]; writes the id to cand[row*L + t] and its log-probability to tok_logp[row*L + t].
+void launch_sample_tokens(const float* logits, int rows, int V, int limit, const double* u, int32_t* cand,
+                          float* tok_logp, int L, int t, int* status, hipStream_t s);
 
 enum GemmEpilogue { EPI_STORE_F32 = 0, EPI_RESIDUAL_ADD = 1 };
 // C[M,N] (float) = A[M,K] * W[N,K]^T, or C += ... (residual add)

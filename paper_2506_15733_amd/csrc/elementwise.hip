@@ -4,10 +4,10 @@
 
 // ---------------------------------------------------------------- embedding
 template <typename T>
-__global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restrict__ E, float* __restrict__ x, int d,
-                             int V, int* status) {
+__global__ void embed_kernel(const int32_t* __restrict__ tok, int tok_stride, const T* __restrict__ E,
+                             float* __restrict__ x, int d, int V, int* status) {
   int m = blockIdx.x;
-  int id = tok[m];
+  int id = tok[(size_t)m * tok_stride];
   if (id < 0 || id >= V) {
     if (threadIdx.x == 0) *status = SPECS_ETOKEN;
     id = id < 0 ? 0 : V - 1;
@@ -17,11 +17,12 @@ __global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restric
   for (int c = threadIdx.x; c < d; c += blockDim.x) xo[c] = to_f32<T>(row[c]);
 }
 template <typename T>
-void launch_embed(const int32_t* tok, const T* E, float* x, int M, int d, int V, int* status, hipStream_t s) {
-  embed_kernel<T><<<M, 256, 0, s>>>(tok, E, x, d, V, status);
+void launch_embed(const int32_t* tok, int tok_stride, const T* E, float* x, int M, int d, int V, int* status,
+                  hipStream_t s) {
+  embed_kernel<T><<<M, 256, 0, s>>>(tok, tok_stride, E, x, d, V, status);
 }
-template void launch_embed<float>(const int32_t*, const float*, float*, int, int, int, int*, hipStream_t);
-template void launch_embed<bf16_t>(const int32_t*, const bf16_t*, float*, int, int, int, int*, hipStream_t);
+template void launch_embed<float>(const int32_t*, int, const float*, float*, int, int, int, int*, hipStream_t);
+template void launch_embed<bf16_t>(const int32_t*, int, const bf16_t*, float*, int, int, int, int*, hipStream_t);
 
 // ---------------------------------------------------------------- RMSNorm
 // One 256-thread block per row. y = x * rsqrt(mean(x^2) + eps) * gain, float math, output in T.
@@ -190,13 +191,13 @@ template void launch_rmsnorm_shifted<bf16_t>(const float*, const float*, const f
 // cos/sin of pos * base^(-2i/hd), pos = context length + t, evaluated in double so that long
 // contexts lose nothing; one table per call, shared by all layers and heads.
 __global__ void rope_table_kernel(float* __restrict__ cs, int M, int nL, int L, int half, int hd, double base,
-                                  const int32_t* __restrict__ lens, int b0, int len_override) {
+                                  const int32_t* __restrict__ lens, int b0, int len_override, int t0) {
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= M * half) return;
   int m = idx / half, i = idx % half;
   int b = m / nL, t = m % L;
   int ctx = len_override >= 0 ? len_override : lens[b0 + b];
-  double ang = (double)(ctx + t) * pow(base, -2.0 * (double)i / (double)hd);
+  double ang = (double)(ctx + t0 + t) * pow(base, -2.0 * (double)i / (double)hd);
   double sn, cn;
   sincos(ang, &sn, &cn);
   cs[(size_t)m * hd + i] = (float)cn;
@@ -206,27 +207,30 @@ void launch_rope_table(float* cs, const BatchGeom& g, int hd, float base, hipStr
   int half = hd / 2;
   int total = g.M * half;
   rope_table_kernel<<<(total + 255) / 256, 256, 0, s>>>(cs, g.M, g.n * g.L, g.L, half, hd, (double)base, g.lens, g.b0,
-                                                        g.len_override);
+                                                        g.len_override, g.t0);
 }
 
-// qkv float [M, Hq+2Hkv, hd] -> q T [M,Hq,hd] (rotated), k T [M,Hkv,hd] (rotated),
-// v T transposed per candidate: vT[cand][Hkv][hd][Lp] (Lp = L rounded up to 16, padding zeroed).
+// qkv float [M, Hq+2Hkv, hd] -> q T [M,Hq,hd] (rotated), k T [cand*Lk + t][Hkv][hd] (rotated),
+// v T transposed per candidate: vT[cand][Hkv][hd][Lp] (Lp = Lk rounded up to 16, padding zeroed), where row m is
+// in-block position t = t0 + m % L of candidate m / L and Lk is the length of a whole block.
 template <typename T>
 __global__ void rope_split_kernel(const float* __restrict__ qkv, const float* __restrict__ cs, T* __restrict__ q,
-                                  T* __restrict__ k, T* __restrict__ vT, int Hq, int Hkv, int hd, int L, int Lp) {
+                                  T* __restrict__ kblk, T* __restrict__ vT, int Hq, int Hkv, int hd, int Lrows, int t0,
+                                  int L, int Lp) {
   size_t m = blockIdx.x;
   int H = Hq + 2 * Hkv, half = hd / 2;
   const float* in = qkv + m * (size_t)H * hd;
   const float* c = cs + m * hd;
-  size_t cand = m / L;
-  int t = (int)(m % L);
+  size_t cand = m / Lrows;
+  int t = t0 + (int)(m % Lrows);
+  const size_t krow = cand * L + t;
   for (int e = threadIdx.x; e < H * half; e += blockDim.x) {
     int h = e / half, i = e % half;
     float x1 = in[h * hd + i], x2 = in[h * hd + half + i];
     if (h < Hq + Hkv) {
       float cn = c[i], sn = c[half + i];
       float y1 = x1 * cn - x2 * sn, y2 = x2 * cn + x1 * sn;
-      T* o = (h < Hq) ? q + (m * Hq + h) * hd : k + (m * Hkv + (h - Hq)) * hd;
+      T* o = (h < Hq) ? q + (m * Hq + h) * hd : kblk + (krow * Hkv + (h - Hq)) * hd;
       o[i] = from_f32<T>(y1);
       o[half + i] = from_f32<T>(y2);
     } else {
@@ -243,7 +247,7 @@ __global__ void rope_split_kernel(const float* __restrict__ qkv, const float* __
 template <typename T>
 void launch_rope_split(const float* qkv, const float* cs, T* q, T* k, T* vT, const BatchGeom& g, int Lp,
                        const ModelDims& md, hipStream_t s) {
-  rope_split_kernel<T><<<g.M, 256, 0, s>>>(qkv, cs, q, k, vT, md.Hq, md.Hkv, md.hd, g.L, Lp);
+  rope_split_kernel<T><<<g.M, 256, 0, s>>>(qkv, cs, q, k, vT, md.Hq, md.Hkv, md.hd, g.L, g.t0, g.Lk, Lp);
 }
 template void launch_rope_split<float>(const float*, const float*, float*, float*, float*, const BatchGeom&, int,
                                        const ModelDims&, hipStream_t);
@@ -332,6 +336,23 @@ void launch_copy_rows(const float* x, float* h_last, const BatchGeom& g, int d, 
   copy_rows_kernel<<<g.B, 256, 0, s>>>(x, h_last, g, d, chosen);
 }
 
+__global__ void broadcast_hlast_kernel(const float* __restrict__ h_last, float* __restrict__ xs, int n, int b0, int d) {
+  size_t r = blockIdx.x;
+  const float* src = h_last + (size_t)(b0 + r / n) * d;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) xs[r * d + c] = src[c];
+}
+void launch_broadcast_hlast(const float* h_last, float* xs, const BatchGeom& g, int d, hipStream_t s) {
+  broadcast_hlast_kernel<<<g.B * g.n, 256, 0, s>>>(h_last, xs, g.n, g.b0, d);
+}
+
+__global__ void scatter_last_rows_kernel(const float* __restrict__ xs, float* __restrict__ x, int L, int d) {
+  size_t c = blockIdx.x;
+  for (int j = threadIdx.x; j < d; j += blockDim.x) x[(c * L + (L - 1)) * d + j] = xs[c * d + j];
+}
+void launch_scatter_last_rows(const float* xs, float* x, int C, int L, int d, hipStream_t s) {
+  scatter_last_rows_kernel<<<C, 256, 0, s>>>(xs, x, L, d);
+}
+
 // ---------------------------------------------------------------- PRM scalar head
 // r[b][i] = sigmoid(w_r . RMSNorm(x at the last block token)), all in float; one block per candidate.
 template <typename T>
@@ -389,6 +410,10 @@ __global__ void block_sum_kernel(const float* __restrict__ tok_logp, float* __re
   double acc = 0.0;
   for (int t = 0; t < L; ++t) acc += (double)tok_logp[(size_t)c * L + t];
   block_out[c] = (float)acc;
+}
+
+void launch_block_sum(const float* tok_logp, float* block_out, int L, int C, hipStream_t s) {
+  block_sum_kernel<<<(C + 63) / 64, 64, 0, s>>>(tok_logp, block_out, L, C);
 }
 
 // tok_scratch: [M] floats used when the caller does not want the per-token terms

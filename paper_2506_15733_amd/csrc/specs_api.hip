@@ -53,6 +53,8 @@ struct Workspace {
   float* zt;         // [R]
   float* tokl;       // [R] per-token log-probs when the caller passes no buffer
   int32_t* chosen;   // [B]
+  float* xs;         // [C, d] residual stream of the one position a generation step processes (LM heads)
+  float* logits;     // [C, V] next-token logits of a generation step (LM heads)
   size_t total;
 };
 
@@ -83,6 +85,9 @@ static Workspace carve(char* base, const specs_model_desc& d, int64_t R, int64_t
   w.zt = (float*)take(R * 4);
   w.tokl = (float*)take(R * 4);
   w.chosen = (int32_t*)take((size_t)(C > 0 ? C : 1) * 4);
+  bool lm = d.head == SPECS_HEAD_LM;
+  w.xs = (float*)take(lm ? (size_t)C * d.d_model * 4 : 0);
+  w.logits = (float*)take(lm ? (size_t)C * d.vocab * 4 : 0);
   w.total = off;
   return w;
 }
@@ -267,6 +272,14 @@ static T* pool_ptr(const specs_prefix* p, const specs_model_desc& d, int layer, 
   return (T*)p->kv_pool + ((size_t)layer * 2 + which) * per;
 }
 
+// Geometry of a launch that covers whole blocks: rows m = (b*n + i)*L + t over all beams of the prefix handle.
+static BatchGeom block_geom(const specs_prefix* p, int n, int L) {
+  BatchGeom g;
+  g.B = p->B; g.n = n; g.L = L; g.M = p->B * n * L; g.b0 = 0; g.len_override = -1; g.t0 = 0; g.Lk = L;
+  g.lens = p->lens_dev; g.page_table = p->page_table; g.max_pages = p->max_pages; g.page_tokens = p->page_tokens;
+  return g;
+}
+
 static ModelDims dims_of(const specs_model_desc& d) {
   ModelDims md;
   md.d = d.d_model; md.Hq = d.n_q_heads; md.Hkv = d.n_kv_heads; md.hd = d.head_dim; md.F = d.ffn; md.V = d.vocab;
@@ -340,19 +353,20 @@ template <typename T>
 static void attention(const T* q, const T* kb, const T* vbT, const T* pK, const T* pV, T* out, const BatchGeom& g,
                       const ModelDims& md, int Lp, int max_ctx, hipStream_t s);
 
-// The trunk over M = B*n*L rows: every row attends to its beam's cached prefix and causally
-// to the earlier rows of its own block. Leaves the final residual stream in ws.x and the
-// per-layer block keys/values in ws.kblk / ws.vblk. commit_pages: also write them into the
-// prefix pages (prefill).
+// The trunk over g.M rows: every row attends to its beam's cached prefix and causally to the earlier
+// positions of its own block. Row m embeds tokens[m * tok_stride]. Leaves the final residual stream in x and the
+// per-layer block keys/values in ws.kblk / ws.vblk (laid out for blocks of g.Lk tokens; a launch with g.L = 1 and
+// g.t0 = t adds position t of every block). commit_pages: also write them into the prefix pages (prefill).
 template <typename T>
 static void run_trunk(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const Workspace& ws,
-                      const BatchGeom& g, const int32_t* tokens, int max_ctx, bool commit_pages, int64_t R, int64_t C,
-                      hipStream_t s) {
+                      const BatchGeom& g, float* x, const int32_t* tokens, int tok_stride, int max_ctx,
+                      bool commit_pages, int64_t R, int64_t C, hipStream_t s) {
   const specs_model_desc& d = m->desc;
   ModelDims md = dims_of(d);
-  const int Lp = round16(g.L);
+  const int Lp = round16(g.Lk);
   int qd = md.Hq * md.hd, kvd = md.Hkv * md.hd;
-  PROFILED(ctx, SPECS_K_OTHER, s, launch_embed<T>(tokens, (const T*)m->w.embed, ws.x, g.M, md.d, md.V, ws.status, s);
+  PROFILED(ctx, SPECS_K_OTHER, s,
+           launch_embed<T>(tokens, tok_stride, (const T*)m->w.embed, x, g.M, md.d, md.V, ws.status, s);
            launch_rope_table(ws.cs, g, md.hd, md.rope_base, s));
   // ws.gu ([R, 2F] floats) is free while the residual projections run (the fused gate/up kernel never writes
   // it, the unfused path has consumed it by then), so it holds their K-split partial products.
@@ -364,7 +378,7 @@ static void run_trunk(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
     T* vb = (T*)ws.vblk + (size_t)l * (R + 16 * C) * kvd;
     T* pK = pool_ptr<T>(p, d, l, 0);
     T* pV = pool_ptr<T>(p, d, l, 1);
-    if (!normed) PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(ws.x, L.g_attn, (T*)ws.a, g.M, md.d, md.eps, s));
+    if (!normed) PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(x, L.g_attn, (T*)ws.a, g.M, md.d, md.eps, s));
     PROFILED(ctx, SPECS_K_QKV, s,
              gemm<T>((const T*)ws.a, (const T*)L.wqkv, ws.qkv, g.M, qd + 2 * kvd, md.d, EPI_STORE_F32, s));
     PROFILED(ctx, SPECS_K_OTHER, s, launch_rope_split<T>(ws.qkv, ws.cs, (T*)ws.q, kb, vb, g, Lp, md, s));
@@ -373,22 +387,22 @@ static void run_trunk(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
     if (commit_pages) launch_kv_commit<T>(kb, vb, pK, pV, g, md, Lp, nullptr, s);
     int parts = 0;
     PROFILED(ctx, SPECS_K_OPROJ, s,
-             parts = gemm_residual_split<T>((const T*)ws.attn, (const T*)L.wo, ws.x, ws.gu, max_split, g.M, md.d, qd, s));
+             parts = gemm_residual_split<T>((const T*)ws.attn, (const T*)L.wo, x, ws.gu, max_split, g.M, md.d, qd, s));
     if (parts)
       PROFILED(ctx, SPECS_K_OTHER, s,
-               launch_add_partials_rmsnorm<T>(ws.x, ws.gu, parts, 0, L.g_ffn, (T*)ws.a, g.M, md.d, md.eps, s));
+               launch_add_partials_rmsnorm<T>(x, ws.gu, parts, 0, L.g_ffn, (T*)ws.a, g.M, md.d, md.eps, s));
     else
-      PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(ws.x, L.g_ffn, (T*)ws.a, g.M, md.d, md.eps, s));
+      PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(x, L.g_ffn, (T*)ws.a, g.M, md.d, md.eps, s));
     PROFILED(ctx, SPECS_K_GATE_UP, s,
              gate_up<T>((const T*)ws.a, (const T*)L.wgu, ws.gu, (T*)ws.act, g.M, md.F, md.d, s));
     PROFILED(ctx, SPECS_K_DOWN, s,
-             parts = gemm_residual_split<T>((const T*)ws.act, (const T*)L.wd, ws.x, ws.gu, max_split, g.M, md.d, md.F, s));
+             parts = gemm_residual_split<T>((const T*)ws.act, (const T*)L.wd, x, ws.gu, max_split, g.M, md.d, md.F, s));
     normed = false;
     if (parts) {
       // the sum of the partials is folded into the next layer's first normalisation (none after the last layer)
       const float* next_gain = l + 1 < d.n_layers ? m->layers[l + 1].g_attn : nullptr;
       PROFILED(ctx, SPECS_K_OTHER, s,
-               launch_add_partials_rmsnorm<T>(ws.x, ws.gu, parts, 0, next_gain, (T*)ws.a, g.M, md.d, md.eps, s));
+               launch_add_partials_rmsnorm<T>(x, ws.gu, parts, 0, next_gain, (T*)ws.a, g.M, md.d, md.eps, s));
       normed = next_gain != nullptr;
     }
   }
@@ -402,13 +416,11 @@ static int score_impl(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
   int64_t C = (int64_t)p->B * n;
   Workspace ws = carve(ctx->workspace, d, R, C);
   if (ws.total > ctx->workspace_bytes) return SPECS_EWORKSPACE;
-  BatchGeom g;
-  g.B = p->B; g.n = n; g.L = L; g.M = (int)R; g.b0 = 0; g.len_override = -1;
-  g.lens = p->lens_dev; g.page_table = p->page_table; g.max_pages = p->max_pages; g.page_tokens = p->page_tokens;
+  BatchGeom g = block_geom(p, n, L);
   int max_ctx = 0;
   for (int b = 0; b < p->B; ++b) max_ctx = p->lens[b] > max_ctx ? p->lens[b] : max_ctx;
   hipStream_t s = ctx->stream;
-  run_trunk<T>(ctx, m, p, ws, g, cand, max_ctx, false, R, C, s);
+  run_trunk<T>(ctx, m, p, ws, g, ws.x, cand, 1, max_ctx, false, R, C, s);
   if (d.head == SPECS_HEAD_LM) {
     int tiles = 0;
     PROFILED(ctx, SPECS_K_OTHER, s,
@@ -444,6 +456,57 @@ extern "C" int specs_score_blocks(specs_ctx* ctx, const specs_model* m, const sp
                                      : score_impl<float>(ctx, m, p, cand, n, L, out, tok_logp);
 }
 
+// Alg. 1, Step I: n blocks of L tokens per beam, one position at a time. Step t: next-token logits from the
+// state that precedes position t (the prefix's last hidden state for t = 0), one token per candidate by inverse
+// CDF from u, then that token goes through the trunk at position t, which adds its keys/values to the block
+// buffers. After the last step the workspace holds what specs_score_blocks(cand) would have left there.
+template <typename T>
+static int generate_impl(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, int n, int L, int limit,
+                         const double* u, int32_t* cand, float* out, float* tok_logp) {
+  const specs_model_desc& d = m->desc;
+  int64_t R = (int64_t)p->B * n * L;
+  int64_t C = (int64_t)p->B * n;
+  Workspace ws = carve(ctx->workspace, d, R, C);
+  if (ws.total > ctx->workspace_bytes) return SPECS_EWORKSPACE;
+  BatchGeom g = block_geom(p, n, 1);                   // one row per candidate
+  g.Lk = L;
+  int max_ctx = 0;
+  for (int b = 0; b < p->B; ++b) max_ctx = p->lens[b] > max_ctx ? p->lens[b] : max_ctx;
+  hipStream_t s = ctx->stream;
+  float* tl = tok_logp ? tok_logp : ws.tokl;
+  launch_broadcast_hlast(p->h_last, ws.xs, g, d.d_model, s);
+  for (int t = 0; t < L; ++t) {
+    g.t0 = t;
+    launch_rmsnorm<T>(ws.xs, m->w.g_final, (T*)ws.a, g.M, d.d_model, d.rms_eps, s);
+    gemm<T>((const T*)ws.a, (const T*)m->w.head, ws.logits, g.M, d.vocab, d.d_model, EPI_STORE_F32, s);
+    launch_sample_tokens(ws.logits, g.M, d.vocab, limit, u, cand, tl, L, t, ws.status, s);
+    run_trunk<T>(ctx, m, p, ws, g, ws.xs, cand + t, L, max_ctx, false, R, C, s);
+  }
+  launch_scatter_last_rows(ws.xs, ws.x, (int)C, L, d.d_model, s);
+  launch_block_sum(tl, out, L, (int)C, s);
+  HIP_TRY(hipGetLastError());
+  ctx->last_model = m;
+  ctx->last_prefix = p;
+  ctx->last_n = n;
+  ctx->last_L = L;
+  return SPECS_OK;
+}
+
+extern "C" int specs_generate_blocks(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, int32_t n, int32_t L,
+                                     int32_t vocab_limit, const double* u, int32_t* cand, float* logp,
+                                     float* tok_logp) {
+  if (!ctx || !m || !p || !u || !cand || !logp) return SPECS_EINVAL;
+  if (p->model != m || m->desc.head != SPECS_HEAD_LM) return SPECS_EINVAL;
+  if (n <= 0 || L <= 0 || vocab_limit < 0 || vocab_limit > m->desc.vocab) return SPECS_EINVAL;
+  if ((int64_t)p->B * n * L > (int64_t)1 << 30) return SPECS_EINVAL;
+  for (int b = 0; b < p->B; ++b)
+    if (p->lens[b] < 1) return SPECS_EINVAL;           // the first token is drawn from the last prefix position
+  HIP_TRY(hipSetDevice(ctx->device));
+  int limit = vocab_limit ? vocab_limit : m->desc.vocab;
+  return m->desc.dtype == SPECS_BF16 ? generate_impl<bf16_t>(ctx, m, p, n, L, limit, u, cand, logp, tok_logp)
+                                     : generate_impl<float>(ctx, m, p, n, L, limit, u, cand, logp, tok_logp);
+}
+
 template <typename T>
 static int prefill_impl(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* tokens) {
   const specs_model_desc& d = m->desc;
@@ -460,10 +523,9 @@ static int prefill_impl(specs_ctx* ctx, const specs_model* m, specs_prefix* p, c
     int len = p->lens[b];
     for (int c0 = 0; c0 < len; c0 += (int)R) {
       int rows = len - c0 < R ? len - c0 : (int)R;
-      BatchGeom g;
-      g.B = 1; g.n = 1; g.L = rows; g.M = rows; g.b0 = b; g.len_override = c0;
-      g.lens = p->lens_dev; g.page_table = p->page_table; g.max_pages = p->max_pages; g.page_tokens = p->page_tokens;
-      run_trunk<T>(ctx, m, p, ws, g, tokens + off + c0, c0, true, R, 1, s);
+      BatchGeom g = block_geom(p, 1, rows);
+      g.B = 1; g.M = rows; g.b0 = b; g.len_override = c0;
+      run_trunk<T>(ctx, m, p, ws, g, ws.x, tokens + off + c0, 1, c0, true, R, 1, s);
       if (c0 + rows == len) launch_copy_rows(ws.x, p->h_last, g, d.d_model, nullptr, s);
     }
     off += len;
@@ -496,9 +558,7 @@ static int commit_impl(specs_ctx* ctx, const specs_model* m, specs_prefix* p, co
   ModelDims md = dims_of(d);
   hipStream_t s = ctx->stream;
   HIP_TRY(hipMemcpyAsync(ws.chosen, chosen_host, sizeof(int32_t) * p->B, hipMemcpyHostToDevice, s));
-  BatchGeom g;
-  g.B = p->B; g.n = n; g.L = L; g.M = (int)R; g.b0 = 0; g.len_override = -1;
-  g.lens = p->lens_dev; g.page_table = p->page_table; g.max_pages = p->max_pages; g.page_tokens = p->page_tokens;
+  BatchGeom g = block_geom(p, n, L);
   size_t kvd = (size_t)md.Hkv * md.hd;
   for (int l = 0; l < d.n_layers; ++l)
     launch_kv_commit<T>((const T*)ws.kblk + (size_t)l * R * kvd, (const T*)ws.vblk + (size_t)l * (R + 16 * C) * kvd,
@@ -597,7 +657,7 @@ extern "C" int specs_op_lmhead_logprob(specs_ctx* ctx, int32_t dtype, const void
                ? lmhead_partials<bf16_t>((const bf16_t*)A, (const bf16_t*)W, tok, pm, ps, zt, M, V, K, ctx->stream)
                : lmhead_partials<float>((const float*)A, (const float*)W, tok, pm, ps, zt, M, V, K, ctx->stream);
   BatchGeom g = {};
-  g.B = 1; g.n = M; g.L = 1; g.M = M;
+  g.B = 1; g.n = M; g.L = 1; g.M = M; g.Lk = 1;
   launch_lmhead_merge(pm, ps, zt, nt, nullptr, tl, tok_logp, g, ctx->stream);
   HIP_TRY(hipGetLastError());
   ctx->last_model = nullptr;
@@ -612,7 +672,9 @@ static void attention(const T* q, const T* kb, const T* vbT, const T* pK, const 
 template <>
 void attention<bf16_t>(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT, const bf16_t* pK, const bf16_t* pV,
                        bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp, int max_ctx, hipStream_t s) {
-  if (!launch_attention_mfma(q, kb, vbT, pK, pV, out, g, md, Lp, s))
+  // the MFMA kernel tiles whole blocks; single-position launches (generation) take the plain kernel
+  bool whole_blocks = g.t0 == 0 && g.Lk == g.L;
+  if (!whole_blocks || !launch_attention_mfma(q, kb, vbT, pK, pV, out, g, md, Lp, s))
     launch_attention_simple<bf16_t>(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, s);
 }
 
@@ -621,9 +683,7 @@ extern "C" int specs_op_attention(specs_ctx* ctx, const specs_model* m, const sp
   if (!ctx || !m || !p || !q || !kb || !vb || !out || n <= 0 || L <= 0) return SPECS_EINVAL;
   if (p->model != m || layer < 0 || layer >= m->desc.n_layers) return SPECS_EINVAL;
   const specs_model_desc& d = m->desc;
-  BatchGeom g;
-  g.B = p->B; g.n = n; g.L = L; g.M = p->B * n * L; g.b0 = 0; g.len_override = -1;
-  g.lens = p->lens_dev; g.page_table = p->page_table; g.max_pages = p->max_pages; g.page_tokens = p->page_tokens;
+  BatchGeom g = block_geom(p, n, L);
   int max_ctx = 0;
   for (int b = 0; b < p->B; ++b) max_ctx = p->lens[b] > max_ctx ? p->lens[b] : max_ctx;
   ModelDims md = dims_of(d);

@@ -1,0 +1,162 @@
+"""Block generation on the GPU (Alg. 1, Step I) against the CPU oracle on the same seeded uniforms.
+
+Tokens are decided by floating-point cumulative sums, so a drawn id may legitimately differ from the oracle's
+where the uniform falls within the arithmetic's tolerance of a boundary of the oracle's interval for its token;
+from that position on the two histories differ and nothing more is compared for that candidate. Everything before
+the first difference must agree (ids exactly, log-probabilities within the scoring tolerances)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workload as W
+from workload.configs import HostWeights, ModelDesc, Workload
+
+pytestmark = pytest.mark.gpu
+
+
+def small_workload(dtype, B=2, n=3, L=6, V=301, page_tokens=4, hd=16, seed=12):
+    t = ModelDesc("target", 2, 6 * hd, 6, 2, hd, 160, V, dtype, "lm")
+    d = ModelDesc("draft", 2, 6 * hd, 6, 3, hd, 96, V, dtype, "lm")
+    p = ModelDesc("prm", 1, 6 * hd, 6, 2, hd, 160, V, dtype, "prm")
+    return Workload("gen", t, d, p, B=B, n=n, L=L, prefix_len=0, lens_range=(7, 70), betas=(1.0,),
+                    token_dist="uniform", page_tokens=page_tokens, seed=seed, u_seed=seed + 1)
+
+
+def gpu_generate(step, role, u, vocab_limit=0):
+    from paper_2506_15733_amd import binding as B
+    wl = step.wl
+    dm, pf = step.models[role], step.prefixes[role]
+    cand = torch.full((wl.B, wl.n, wl.L), -1, dtype=torch.int32, device=step.device)
+    logp = torch.zeros((wl.B, wl.n), dtype=torch.float32, device=step.device)
+    tok = torch.zeros((wl.B, wl.n, wl.L), dtype=torch.float32, device=step.device)
+    ud = torch.from_numpy(u).to(step.device)
+    with torch.cuda.stream(step.role_streams[role]):
+        step.role_streams[role].wait_stream(step.stream)
+        B.specs_generate_blocks(dm.ctx, dm.model, pf.handle, ud, cand, logp, tok, vocab_limit)
+    torch.cuda.synchronize()
+    assert B.specs_ctx_status(dm.ctx) == 0
+    return cand.cpu().numpy(), logp.cpu().numpy(), tok.cpu().numpy()
+
+
+def compare_generation(cand, tok, logp, o_tokens, o_tok, o_blk, o_bounds, u, tol_lp, eta):
+    """Returns the fraction of token positions compared (those before a candidate's first differing id)."""
+    n, L = o_tokens.shape
+    compared = 0
+    for i in range(n):
+        diff = np.nonzero(cand[i] != o_tokens[i])[0]
+        first = int(diff[0]) if len(diff) else L
+        assert np.abs(tok[i, :first] - o_tok[i, :first]).max(initial=0.0) < tol_lp, (i, first)
+        compared += first
+        if first == L:
+            assert abs(logp[i] - o_blk[i]) < tol_lp * max(1.0, np.sqrt(L)), i
+            continue
+        lo, hi = o_bounds[i, first]
+        near = min(u[i, first] - lo, hi - u[i, first])
+        assert near <= eta, (i, first, near, int(cand[i, first]), int(o_tokens[i, first]))
+        assert abs(int(cand[i, first]) - int(o_tokens[i, first])) == 1, (i, first)
+    return compared / (n * L)
+
+
+@pytest.mark.parametrize("dtype,role", [("f32", "draft"), ("f32", "target"), ("bf16", "draft")])
+def test_generated_blocks_match_the_oracle(dtype, role):
+    from paper_2506_15733_amd import synthetic
+    wl = small_workload(dtype)
+    step = synthetic.ScoringStep(wl)
+    step.prefill()
+    desc = wl.models()[role]
+    u = W.rng.uniform_f64(wl.u_seed, "gen/u", wl.B * wl.n * wl.L).reshape(wl.B, wl.n, wl.L)
+    cand, logp, tok = gpu_generate(step, role, u)
+    hw = HostWeights(desc, wl.seed)
+    caches = oracle.prefill(desc, hw, wl.prefix_tokens())
+    tol, eta = (1e-5, 1e-5) if dtype == "f32" else (2e-2, 4e-2)
+    frac = []
+    for b in range(wl.B):
+        o_tokens, o_tok, o_blk, _, o_bounds = oracle.generate_blocks(desc, hw, caches[b], wl.n, wl.L, u[b])
+        frac.append(compare_generation(cand[b], tok[b], logp[b], o_tokens, o_tok, o_blk, o_bounds, u[b], tol, eta))
+    assert np.mean(frac) > (0.99 if dtype == "f32" else 0.5), frac
+    assert len(np.unique(cand)) > 10
+    step.close()
+
+
+def test_generation_then_commit_then_scoring_matches_the_oracle():
+    """The context is left as after a scoring call: committing a generated block and scoring the next candidates
+    against the extended trace must agree with the oracle run over [tr, Y_chosen]."""
+    from paper_2506_15733_amd import synthetic, binding as B
+    wl = small_workload("f32", seed=15)
+    step = synthetic.ScoringStep(wl, extra_tokens=wl.L)
+    step.prefill()
+    u = W.rng.uniform_f64(wl.u_seed, "gen/u2", wl.B * wl.n * wl.L).reshape(wl.B, wl.n, wl.L)
+    cand, _, _ = gpu_generate(step, "draft", u)
+    desc = wl.draft
+    hw = HostWeights(desc, wl.seed)
+    caches = oracle.prefill(desc, hw, wl.prefix_tokens())
+    chosen = [1, 2][:wl.B]
+    traces = []
+    for b in range(wl.B):
+        o_tokens = oracle.generate_blocks(desc, hw, caches[b], wl.n, wl.L, u[b])[0]
+        assert np.array_equal(o_tokens, cand[b])            # float configuration, seeds chosen free of boundary cases
+        traces.append(np.concatenate([wl.prefix_tokens()[b], o_tokens[chosen[b]]]))
+    dm, pf = step.models["draft"], step.prefixes["draft"]
+    B.specs_commit_block(dm.ctx, dm.model, pf.handle, chosen)
+    nxt = wl.candidates()
+    step.cand = torch.from_numpy(nxt).to(step.device)
+    step.score("draft")
+    torch.cuda.synchronize()
+    want_blk, want_tok = oracle.score_cached(desc, hw, oracle.prefill(desc, hw, traces), nxt)
+    assert np.abs(step.out["draft"].cpu().numpy() - want_blk).max() < 1e-5
+    assert np.abs(step.tok["draft"].cpu().numpy() - want_tok).max() < 1e-5
+    step.close()
+
+
+def test_vocabulary_limit_and_bad_uniforms():
+    from paper_2506_15733_amd import synthetic, binding as B
+    wl = small_workload("f32", B=1, n=4, L=3)
+    step = synthetic.ScoringStep(wl)
+    step.prefill()
+    u = W.rng.uniform_f64(5, "gen/u3", wl.n * wl.L).reshape(1, wl.n, wl.L)
+    u[0, 0, 0] = np.nextafter(1.0, 0)                       # the largest uniform draws the last permitted id
+    limit = 37
+    cand, logp, tok = gpu_generate(step, "draft", u, vocab_limit=limit)
+    assert cand.max() < limit and cand[0, 0, 0] == limit - 1
+    hw = HostWeights(wl.draft, wl.seed)
+    cache = oracle.prefill(wl.draft, hw, wl.prefix_tokens())[0]
+    o_tokens, o_tok, o_blk, _, _ = oracle.generate_blocks(wl.draft, hw, cache, wl.n, wl.L, u[0], vocab_limit=limit)
+    assert np.array_equal(o_tokens, cand[0])
+    assert np.abs(o_tok - tok[0]).max() < 1e-5 and np.abs(o_blk - logp[0]).max() < 1e-5
+    # a uniform outside [0,1) is reported through the status word
+    dm, pf = step.models["draft"], step.prefixes["draft"]
+    bad = torch.from_numpy(np.full((1, wl.n, wl.L), 1.0)).to(step.device)
+    c = torch.zeros((1, wl.n, wl.L), dtype=torch.int32, device=step.device)
+    lp = torch.zeros((1, wl.n), dtype=torch.float32, device=step.device)
+    with torch.cuda.stream(step.role_streams["draft"]):
+        B.specs_generate_blocks(dm.ctx, dm.model, pf.handle, bad, c, lp)
+    torch.cuda.synchronize()
+    assert B.specs_ctx_status(dm.ctx) == 4                   # SPECS_ERANGE
+    with pytest.raises(B.SpecsError):                        # a PRM cannot generate
+        B.specs_generate_blocks(step.models["prm"].ctx, step.models["prm"].model, step.prefixes["prm"].handle, bad, c, lp)
+    step.close()
+
+
+def test_generation_log_probs_equal_block_scoring_of_the_same_tokens_bf16_mfma_shapes():
+    """Property that holds at any size: the log-likelihood emitted while generating equals what the scoring pass
+    (block-parallel kernels, MFMA path) assigns to the same tokens, within the bf16 tolerance."""
+    from paper_2506_15733_amd import synthetic
+    t = ModelDesc("target", 2, 192, 3, 1, 64, 320, 1000, "bf16", "lm")
+    d = ModelDesc("draft", 2, 128, 2, 2, 64, 192, 1000, "bf16", "lm")
+    p = ModelDesc("prm", 1, 192, 3, 1, 64, 320, 1000, "bf16", "prm")
+    wl = Workload("gen_mfma", t, d, p, B=2, n=5, L=19, prefix_len=0, lens_range=(40, 300), betas=(1.0,),
+                  token_dist="zipf", page_tokens=16, seed=14, u_seed=12)
+    step = synthetic.ScoringStep(wl)
+    step.prefill()
+    u = W.rng.uniform_f64(wl.u_seed, "gen/u4", wl.B * wl.n * wl.L).reshape(wl.B, wl.n, wl.L)
+    for role in ("draft", "target"):
+        cand, logp, tok = gpu_generate(step, role, u)
+        step.cand = torch.from_numpy(cand).to(step.device)
+        step.score(role)
+        torch.cuda.synchronize()
+        assert np.abs(step.tok[role].cpu().numpy() - tok).max() < 2e-2
+        assert np.abs(step.out[role].cpu().numpy() - logp).max() < 2e-2 * np.sqrt(wl.L)
+    step.close()

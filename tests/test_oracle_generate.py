@@ -28,6 +28,7 @@ def test_inverse_cdf_closed_forms():
     k, lp = oracle.sample_token(z, 0.3)
     assert math.isclose(lp, math.log(2 / 6), rel_tol=1e-12)
     assert oracle.sample_token(np.array([-np.inf, 0.0, -np.inf]), 0.0)[0] == 1          # zero-weight ids are never drawn
+    assert np.allclose(oracle.sample_token(z, 0.3, with_interval=True)[2], (1 / 6, 1 / 2), atol=1e-15)
     with pytest.raises(ValueError):
         oracle.sample_token(z, 1.0)
     grid = (np.arange(1 << 12) + 0.5) / (1 << 12)
@@ -49,7 +50,7 @@ def test_joint_law_of_a_generated_block_is_the_block_likelihood():
     G = 96
     g = (np.arange(G) + 0.5) / G
     u = np.stack(np.meshgrid(g, g, indexing="ij"), -1).reshape(-1, 2)
-    tokens, tok_lp, blk, _ = oracle.generate_blocks(desc, hw, cache, len(u), 2, u)
+    tokens, tok_lp, blk, _, _ = oracle.generate_blocks(desc, hw, cache, len(u), 2, u)
     area = np.zeros(9)
     for (a, b), lp in zip(tokens, blk):
         area[a * 3 + b] += 1.0 / len(u)
@@ -69,7 +70,8 @@ def test_generated_blocks_rescore_to_the_same_log_probabilities(dtype):
     cache = oracle.prefill(desc, hw, [tr])[0]
     n, L = 3, 6
     u = W.rng.uniform_f64(3, "gen/u", n * L).reshape(n, L)
-    tokens, tok_lp, blk, caches = oracle.generate_blocks(desc, hw, cache, n, L, u)
+    tokens, tok_lp, blk, caches, bounds = oracle.generate_blocks(desc, hw, cache, n, L, u)
+    assert np.all((bounds[..., 0] <= u) & (u < bounds[..., 1]))
     blk2, tok2 = oracle.score_cached(desc, hw, [cache], tokens[None])
     tol = 1e-9 if dtype == "f32" else 1e-9        # same rounding points, same operands: the two paths agree
     assert np.abs(tok2[0] - tok_lp).max() < tol and np.abs(blk2[0] - blk).max() < tol * L

@@ -133,6 +133,56 @@ def kernel_bench(args):
                       "frac_mfma_peak": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}))
 
 
+def model_bytes(d):
+    """bf16 bytes a decoding step must stream: every layer's matrices and the vocabulary head (embedding rows are
+    gathered, not streamed)."""
+    qd, kvd = d.n_q_heads * d.head_dim, d.n_kv_heads * d.head_dim
+    per_layer = d.d_model * (qd + 2 * kvd) + qd * d.d_model + 3 * d.d_model * d.ffn
+    es = 2 if d.dtype == "bf16" else 4
+    return es * (d.n_layers * per_layer + d.vocab * d.d_model)
+
+
+def generate_bench(args):
+    """Block generation by one model: n blocks of L tokens per beam, token by token. The step streams the whole
+    model once per token position, so the binding roof is HBM bandwidth."""
+    import numpy as np
+    import torch
+    import workload as W
+    from paper_2506_15733_amd import synthetic, binding as B
+    wl = W.get_config(args.workload)
+    role = args.generate
+    step = synthetic.ScoringStep(wl, device="cuda:0", concurrent=False)
+    step.prefill()
+    dm, pf = step.models[role], step.prefixes[role]
+    u = torch.from_numpy(W.rng.uniform_f64(wl.u_seed, "bench/gen", wl.B * wl.n * wl.L).reshape(wl.B, wl.n, wl.L)).cuda()
+    cand = torch.zeros((wl.B, wl.n, wl.L), dtype=torch.int32, device="cuda:0")
+    logp = torch.zeros((wl.B, wl.n), dtype=torch.float32, device="cuda:0")
+    limit = min(m.vocab for m in wl.models().values() if m.head == "lm")
+    run = lambda: B.specs_generate_blocks(dm.ctx, dm.model, pf.handle, u, cand, logp, None, limit)
+    run()
+    torch.cuda.synchronize()
+    assert B.specs_ctx_status(dm.ctx) == 0
+    t0 = time.perf_counter()
+    for _ in range(args.reps):
+        run()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.reps
+    B.specs_ctx_profile(dm.ctx, True)
+    run()
+    prof = B.specs_ctx_profile_read(dm.ctx)
+    B.specs_ctx_profile(dm.ctx, False)
+    d = wl.models()[role]
+    streamed = model_bytes(d) * wl.L
+    line = {"metric": "generated candidate tokens/sec (n blocks x L) on 1 MI355X", "value": wl.B * wl.n * wl.L / dt,
+            "unit": "tokens/s", "ms_per_block_set": dt * 1e3, "ms_per_position": dt * 1e3 / wl.L,
+            "config": {"workload": wl.name, "generator": role, "B": wl.B, "n": wl.n, "L": wl.L},
+            "roofline": {"bound": "hbm", "achieved": streamed / dt / 1e9, "peak": 8000.0, "unit": "GB/s",
+                         "frac": streamed / dt / 1e9 / 8000.0, "bytes_per_position": model_bytes(d)},
+            "kernel_ms_per_position": {k: ms / wl.L for k, (ms, n) in prof.items()},
+            "kernel_launches_per_position": {k: n / wl.L for k, (ms, n) in prof.items()}}
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--kernel", default=None, help="gate_up|qkv|o|down|lmhead|attn|copy: time that kernel alone")
@@ -143,9 +193,12 @@ def main():
     ap.add_argument("--workload", default="c4_7b")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--serial", action="store_true", help="one stream for the three passes instead of one each")
+    ap.add_argument("--generate", default=None, help="draft|target: time block generation (Alg. 1 Step I) by that model")
     args = ap.parse_args()
     if args.kernel:
         return kernel_bench(args)
+    if args.generate:
+        return generate_bench(args)
     if args.gpus != 1:
         print("bench.py measures the one-GPU share of the path; --gpus must be 1 (nothing here uses a second GPU)",
               file=sys.stderr)

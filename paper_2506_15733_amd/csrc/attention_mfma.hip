@@ -39,6 +39,12 @@ struct AttnArgs {
   BatchGeom g;
   int Hq, Hkv, Lp, q_tiles, total_wg, wg_per_xcd;
   float scale_log2e;
+  // single-position launches (generation): the prefix keys are cut into n_splits runs of tiles and every
+  // workgroup leaves an un-normalised partial result for a second kernel to merge
+  int n_splits;
+  float* part_o;        // [(b*Hkv + kvh)][q_tile][split][128][HD]
+  float* part_m;        // [..][128] running maximum (log2 domain), -inf if the run was empty
+  float* part_l;        // [..][128] sum of weights relative to that maximum
 };
 
 template <int HD>
@@ -46,7 +52,11 @@ __device__ __forceinline__ int k_swizzle(int row, int chunk) {
   return HD == 128 ? (chunk ^ (row & 15)) : (chunk ^ ((row >> 1) & 7));
 }
 
-template <int HD, int QT>
+// DEC = false: whole blocks, as described above. DEC = true: one position per candidate; the stacked rows of a
+// (beam, kv head) are its n candidates x g query heads (row r = i*g + j), the workgroup covers only the prefix
+// tiles of its split and writes (O un-normalised, m, l) instead of the output; the candidate's own block keys
+// are added by the merge kernel.
+template <int HD, int QT, bool DEC>
 __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(AttnArgs a) {
   constexpr int KROW = HD * 2;              // bytes per key row
   constexpr int KCH = HD / 8;               // 16-byte chunks per key row
@@ -64,8 +74,11 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
   const BatchGeom& G = a.g;
   const int g = a.Hq / a.Hkv;
   int rem = logical;
+  int split = 0;
+  if (DEC) { split = rem % a.n_splits; rem /= a.n_splits; }
   const int qt_idx = rem % a.q_tiles; rem /= a.q_tiles;
-  const int cand = rem % G.n; rem /= G.n;
+  int cand = 0;
+  if (!DEC) { cand = rem % G.n; rem /= G.n; }
   const int kvh = rem % a.Hkv;
   const int b = rem / a.Hkv;
 
@@ -75,7 +88,7 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
   const int L = G.L;
   const int cand_idx = b * G.n + cand;
   const size_t m_c0 = (size_t)cand_idx * L;                 // first row of this candidate
-  const int rows_total = L * g;
+  const int rows_total = DEC ? G.n * g : L * g;
   const int r_wg0 = qt_idx * BQ;
   const int32_t* ptab = G.page_table + (size_t)(G.b0 + b) * G.max_pages;
 
@@ -86,9 +99,10 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
   for (int u = 0; u < QT; ++u) {
     int r = r_wg0 + (wave * QT + u) * 32 + lq;
     int rc = r < rows_total ? r : rows_total - 1;
-    int t = rc / g, j = rc - t * g;
+    int t = rc / g, j = rc - t * g;                 // DEC: t is the candidate index within the beam
     tq[u] = t;
-    const bf16_t* src = a.q + ((m_c0 + t) * a.Hq + (size_t)kvh * g + j) * HD;
+    const size_t qrow = DEC ? (size_t)b * G.n + t : m_c0 + t;
+    const bf16_t* src = a.q + (qrow * a.Hq + (size_t)kvh * g + j) * HD;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[u][ks] = *(const bf16x8*)(src + ks * 16 + lh * 8);
   }
@@ -109,8 +123,10 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
   const int n_pages = (P + 15) >> 4;
   int t_hi = (r_wg0 + BQ - 1) / g;
   t_hi = t_hi < L - 1 ? t_hi : L - 1;
-  const int n_btiles = (r_wg0 < rows_total) ? (t_hi >> 6) + 1 : 0;
-  const int n_tiles = n_ptiles + n_btiles;
+  const int n_btiles = DEC ? 0 : ((r_wg0 < rows_total) ? (t_hi >> 6) + 1 : 0);
+  // tiles [tile_lo, tile_lo + n_tiles) of the list (prefix tiles, then block tiles)
+  const int tile_lo = DEC ? (int)((long)split * n_ptiles / a.n_splits) : 0;
+  const int n_tiles = DEC ? (int)((long)(split + 1) * n_ptiles / a.n_splits) - tile_lo : n_ptiles + n_btiles;
 
   // one wavefront stages one 16-key group (a page, or 16 block tokens) of the tile: K rows and V^T
   auto stage_tile = [&](int tile, char* buf) {
@@ -159,15 +175,16 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
     }
   };
 
-  if (n_tiles > 0) stage_tile(0, smem);
+  if (n_tiles > 0) stage_tile(tile_lo, smem);
   // pi(i): A-row i of the S^T product carries key pi(i) of the 32-key half tile
   const int pi_row = (lq & 16) | ((lq & 4) << 1) | ((lq & 8) >> 1) | (lq & 3);
 
-  for (int tile = 0; tile < n_tiles; ++tile) {
+  for (int it = 0; it < n_tiles; ++it) {
+    const int tile = tile_lo + it;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (tile + 1 < n_tiles) stage_tile(tile + 1, smem + ((tile + 1) & 1) * STAGE);
-    const char* Ks = smem + (tile & 1) * STAGE;
+    if (it + 1 < n_tiles) stage_tile(tile + 1, smem + ((it + 1) & 1) * STAGE);
+    const char* Ks = smem + (it & 1) * STAGE;
     const char* Vs = Ks + K_BYTES;
     const bool is_block = tile >= n_ptiles;
     const int key_base = is_block ? (tile - n_ptiles) * 64 : tile * 64;
@@ -253,7 +270,19 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
   for (int u = 0; u < QT; ++u) {
     int r = r_wg0 + (wave * QT + u) * 32 + lq;
     float l = l_run[u] + __shfl_xor(l_run[u], 32, 64);
-    if (r < rows_total) {
+    if (DEC) {
+      const size_t prow = ((((size_t)b * a.Hkv + kvh) * a.q_tiles + qt_idx) * a.n_splits + split) * 128 +
+                          (wave * QT + u) * 32 + lq;
+      if (lh == 0) { a.part_m[prow] = m_run[u]; a.part_l[prow] = l; }
+      float* dst = a.part_o + prow * HD;
+#pragma unroll
+      for (int dt = 0; dt < NI; ++dt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          float4 v = {o[u][dt][r4 * 4], o[u][dt][r4 * 4 + 1], o[u][dt][r4 * 4 + 2], o[u][dt][r4 * 4 + 3]};
+          *(float4*)(dst + dt * 32 + 8 * r4 + 4 * lh) = v;
+        }
+    } else if (r < rows_total) {
       int t = r / g, j = r - t * g;
       float inv = 1.0f / l;
       bf16_t* dst = a.out + ((m_c0 + t) * a.Hq + (size_t)kvh * g + j) * HD;
@@ -269,16 +298,16 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
   }
 }
 
-template <int HD, int QT>
+template <int HD, int QT, bool DEC = false>
 static void launch_attn_variant(const AttnArgs& a, hipStream_t s) {
   constexpr int smem = 2 * (64 * HD * 2 + 4 * HD * 32);
   static bool configured = false;
   if (!configured) {
-    (void)hipFuncSetAttribute((const void*)attention_mfma_kernel<HD, QT>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              smem);
+    (void)hipFuncSetAttribute((const void*)attention_mfma_kernel<HD, QT, DEC>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     configured = true;
   }
-  attention_mfma_kernel<HD, QT><<<dim3(a.wg_per_xcd * 8), 256, smem, s>>>(a);
+  attention_mfma_kernel<HD, QT, DEC><<<dim3(a.wg_per_xcd * 8), 256, smem, s>>>(a);
 }
 
 // Returns false if the shape is not one this kernel takes (head_dim 64/128, 16-token pages).
@@ -289,6 +318,7 @@ bool launch_attention_mfma(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT,
   AttnArgs a;
   a.q = q; a.kb = kb; a.vbT = vbT; a.poolK = poolK; a.poolV = poolV; a.out = out; a.g = g;
   a.Hq = md.Hq; a.Hkv = md.Hkv; a.Lp = Lp;
+  a.n_splits = 1; a.part_o = nullptr; a.part_m = nullptr; a.part_l = nullptr;
   a.scale_log2e = 1.4426950408889634f / sqrtf((float)md.hd);
   int rows = g.L * (md.Hq / md.Hkv);
   // 256-row workgroups only when they waste less padding than 128-row ones (the latter run two per CU)
@@ -299,5 +329,40 @@ bool launch_attention_mfma(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT,
   a.wg_per_xcd = (a.total_wg + 7) / 8;
   if (md.hd == 128) { if (big) launch_attn_variant<128, 2>(a, s); else launch_attn_variant<128, 1>(a, s); }
   else { if (big) launch_attn_variant<64, 2>(a, s); else launch_attn_variant<64, 1>(a, s); }
+  return true;
+}
+
+// Prefix part of a single-position launch (g.L == 1): partial results per (beam, kv head, row tile, split).
+// q_tiles_out / n_splits_out describe the partial buffers' layout to the merge kernel. part_floats: room in
+// `part` (floats); returns false if the shape is not taken or the partials would not fit.
+bool launch_attention_mfma_decode_prefix(const bf16_t* q, const bf16_t* poolK, const bf16_t* poolV, const BatchGeom& g,
+                                         const ModelDims& md, int max_ctx, float* part, size_t part_floats,
+                                         int* q_tiles_out, int* n_splits_out, hipStream_t s) {
+  if ((md.hd != 64 && md.hd != 128) || g.page_tokens != 16 || g.L != 1) return false;
+  AttnArgs a;
+  a.q = q; a.kb = nullptr; a.vbT = nullptr; a.poolK = poolK; a.poolV = poolV; a.out = nullptr; a.g = g;
+  a.Hq = md.Hq; a.Hkv = md.Hkv; a.Lp = 16;
+  a.scale_log2e = 1.4426950408889634f / sqrtf((float)md.hd);
+  int rows = g.n * (md.Hq / md.Hkv);
+  a.q_tiles = (rows + 127) / 128;
+  int base = g.B * md.Hkv * a.q_tiles;
+  int max_tiles = (max_ctx + 63) / 64;
+  int splits = (512 + base - 1) / base;                 // about two workgroups per CU
+  splits = splits > max_tiles ? max_tiles : splits;
+  splits = splits < 1 ? 1 : splits;
+  size_t per_split = (size_t)base * 128 * (md.hd + 2);
+  if (per_split > part_floats) return false;
+  if ((size_t)splits * per_split > part_floats) splits = (int)(part_floats / per_split);
+  a.n_splits = splits;
+  size_t rows_all = (size_t)base * splits * 128;
+  a.part_o = part;
+  a.part_m = part + rows_all * md.hd;
+  a.part_l = a.part_m + rows_all;
+  a.total_wg = base * splits;
+  a.wg_per_xcd = (a.total_wg + 7) / 8;
+  if (md.hd == 128) launch_attn_variant<128, 1, true>(a, s);
+  else launch_attn_variant<64, 1, true>(a, s);
+  *q_tiles_out = a.q_tiles;
+  *n_splits_out = splits;
   return true;
 }

@@ -95,6 +95,12 @@ bool launch_attention_mfma(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT,
                            const bf16_t* poolV, bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp,
                            hipStream_t s);
 
+// One in-block position per candidate (g.L == 1, position g.t0): prefix keys by the MFMA kernel in split mode,
+// merged with the candidate's own block keys. part: scratch of part_floats floats. False if the shape is not taken.
+bool launch_attention_decode(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT, const bf16_t* poolK,
+                             const bf16_t* poolV, bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp,
+                             int max_ctx, float* part, size_t part_floats, hipStream_t s);
+
 // Fused vocabulary head: per (row, 64-column tile) partial (max, sum exp) and the target-token logit.
 template <typename T>
 void launch_lmhead_partials_simple(const T* A, const T* W, const int32_t* tok, float* part_max, float* part_sum,

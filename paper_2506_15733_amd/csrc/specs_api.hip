@@ -349,9 +349,10 @@ int lmhead_partials<bf16_t>(const bf16_t* A, const bf16_t* W, const int32_t* tok
   return tiles;
 }
 
+// scratch: floats free for the duration of the call (partial results of single-position launches)
 template <typename T>
 static void attention(const T* q, const T* kb, const T* vbT, const T* pK, const T* pV, T* out, const BatchGeom& g,
-                      const ModelDims& md, int Lp, int max_ctx, hipStream_t s);
+                      const ModelDims& md, int Lp, int max_ctx, float* scratch, size_t scratch_floats, hipStream_t s);
 
 // The trunk over g.M rows: every row attends to its beam's cached prefix and causally to the earlier
 // positions of its own block. Row m embeds tokens[m * tok_stride]. Leaves the final residual stream in x and the
@@ -383,7 +384,8 @@ static void run_trunk(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
              gemm<T>((const T*)ws.a, (const T*)L.wqkv, ws.qkv, g.M, qd + 2 * kvd, md.d, EPI_STORE_F32, s));
     PROFILED(ctx, SPECS_K_OTHER, s, launch_rope_split<T>(ws.qkv, ws.cs, (T*)ws.q, kb, vb, g, Lp, md, s));
     PROFILED(ctx, SPECS_K_ATTENTION, s,
-             attention<T>((const T*)ws.q, kb, vb, pK, pV, (T*)ws.attn, g, md, Lp, max_ctx, s));
+             attention<T>((const T*)ws.q, kb, vb, pK, pV, (T*)ws.attn, g, md, Lp, max_ctx, ws.gu,
+                          (size_t)R * 2 * md.F, s));
     if (commit_pages) launch_kv_commit<T>(kb, vb, pK, pV, g, md, Lp, nullptr, s);
     int parts = 0;
     PROFILED(ctx, SPECS_K_OPROJ, s,
@@ -477,9 +479,11 @@ static int generate_impl(specs_ctx* ctx, const specs_model* m, const specs_prefi
   launch_broadcast_hlast(p->h_last, ws.xs, g, d.d_model, s);
   for (int t = 0; t < L; ++t) {
     g.t0 = t;
-    launch_rmsnorm<T>(ws.xs, m->w.g_final, (T*)ws.a, g.M, d.d_model, d.rms_eps, s);
-    gemm<T>((const T*)ws.a, (const T*)m->w.head, ws.logits, g.M, d.vocab, d.d_model, EPI_STORE_F32, s);
-    launch_sample_tokens(ws.logits, g.M, d.vocab, limit, u, cand, tl, L, t, ws.status, s);
+    PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(ws.xs, m->w.g_final, (T*)ws.a, g.M, d.d_model, d.rms_eps, s));
+    PROFILED(ctx, SPECS_K_LMHEAD, s,
+             gemm<T>((const T*)ws.a, (const T*)m->w.head, ws.logits, g.M, d.vocab, d.d_model, EPI_STORE_F32, s));
+    PROFILED(ctx, SPECS_K_OTHER, s,
+             launch_sample_tokens(ws.logits, g.M, d.vocab, limit, u, cand, tl, L, t, ws.status, s));
     run_trunk<T>(ctx, m, p, ws, g, ws.xs, cand + t, L, max_ctx, false, R, C, s);
   }
   launch_scatter_last_rows(ws.xs, ws.x, (int)C, L, d.d_model, s);
@@ -666,16 +670,19 @@ extern "C" int specs_op_lmhead_logprob(specs_ctx* ctx, int32_t dtype, const void
 
 template <typename T>
 static void attention(const T* q, const T* kb, const T* vbT, const T* pK, const T* pV, T* out, const BatchGeom& g,
-                      const ModelDims& md, int Lp, int max_ctx, hipStream_t s) {
+                      const ModelDims& md, int Lp, int max_ctx, float* scratch, size_t scratch_floats, hipStream_t s) {
   launch_attention_simple<T>(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, s);
 }
 template <>
 void attention<bf16_t>(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT, const bf16_t* pK, const bf16_t* pV,
-                       bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp, int max_ctx, hipStream_t s) {
-  // the MFMA kernel tiles whole blocks; single-position launches (generation) take the plain kernel
+                       bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp, int max_ctx, float* scratch,
+                       size_t scratch_floats, hipStream_t s) {
   bool whole_blocks = g.t0 == 0 && g.Lk == g.L;
-  if (!whole_blocks || !launch_attention_mfma(q, kb, vbT, pK, pV, out, g, md, Lp, s))
-    launch_attention_simple<bf16_t>(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, s);
+  bool done = whole_blocks ? launch_attention_mfma(q, kb, vbT, pK, pV, out, g, md, Lp, s)
+                           : (g.L == 1 && scratch &&
+                              launch_attention_decode(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, scratch,
+                                                      scratch_floats, s));
+  if (!done) launch_attention_simple<bf16_t>(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, s);
 }
 
 extern "C" int specs_op_attention(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, int32_t layer,
@@ -695,11 +702,11 @@ extern "C" int specs_op_attention(specs_ctx* ctx, const specs_model* m, const sp
   if (d.dtype == SPECS_BF16) {
     launch_transpose_v<bf16_t>((const bf16_t*)vb, (bf16_t*)vT, cands, md.Hkv, md.hd, L, Lp, ctx->stream);
     attention<bf16_t>((const bf16_t*)q, (const bf16_t*)kb, (const bf16_t*)vT, pool_ptr<bf16_t>(p, d, layer, 0),
-                      pool_ptr<bf16_t>(p, d, layer, 1), (bf16_t*)out, g, md, Lp, max_ctx, ctx->stream);
+                      pool_ptr<bf16_t>(p, d, layer, 1), (bf16_t*)out, g, md, Lp, max_ctx, nullptr, 0, ctx->stream);
   } else {
     launch_transpose_v<float>((const float*)vb, (float*)vT, cands, md.Hkv, md.hd, L, Lp, ctx->stream);
     attention<float>((const float*)q, (const float*)kb, (const float*)vT, pool_ptr<float>(p, d, layer, 0),
-                     pool_ptr<float>(p, d, layer, 1), (float*)out, g, md, Lp, max_ctx, ctx->stream);
+                     pool_ptr<float>(p, d, layer, 1), (float*)out, g, md, Lp, max_ctx, nullptr, 0, ctx->stream);
   }
   HIP_TRY(hipGetLastError());
   ctx->last_model = nullptr;

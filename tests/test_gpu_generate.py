@@ -60,10 +60,21 @@ def compare_generation(cand, tok, logp, o_tokens, o_tok, o_blk, o_bounds, u, tol
     return compared / (n * L)
 
 
-@pytest.mark.parametrize("dtype,role", [("f32", "draft"), ("f32", "target"), ("bf16", "draft")])
+def mfma_workload():
+    """bf16 shapes the MFMA kernels take (K % 64 == 0, head_dim 64, 16-token pages), ragged otherwise; n * g = 15
+    and 10 stacked rows, prefixes of several tiles."""
+    t = ModelDesc("target", 2, 192, 3, 1, 64, 320, 1000, "bf16", "lm")
+    d = ModelDesc("draft", 2, 128, 2, 2, 64, 192, 1000, "bf16", "lm")
+    p = ModelDesc("prm", 1, 192, 3, 1, 64, 320, 1000, "bf16", "prm")
+    return Workload("gen_mfma", t, d, p, B=2, n=5, L=19, prefix_len=0, lens_range=(40, 300), betas=(1.0,),
+                    token_dist="zipf", page_tokens=16, seed=14, u_seed=12)
+
+
+@pytest.mark.parametrize("dtype,role", [("f32", "draft"), ("f32", "target"), ("bf16", "draft"), ("bf16_mfma", "draft"),
+                                        ("bf16_mfma", "target")])
 def test_generated_blocks_match_the_oracle(dtype, role):
     from paper_2506_15733_amd import synthetic
-    wl = small_workload(dtype)
+    wl = mfma_workload() if dtype == "bf16_mfma" else small_workload(dtype)
     step = synthetic.ScoringStep(wl)
     step.prefill()
     desc = wl.models()[role]
@@ -144,11 +155,7 @@ def test_generation_log_probs_equal_block_scoring_of_the_same_tokens_bf16_mfma_s
     """Property that holds at any size: the log-likelihood emitted while generating equals what the scoring pass
     (block-parallel kernels, MFMA path) assigns to the same tokens, within the bf16 tolerance."""
     from paper_2506_15733_amd import synthetic
-    t = ModelDesc("target", 2, 192, 3, 1, 64, 320, 1000, "bf16", "lm")
-    d = ModelDesc("draft", 2, 128, 2, 2, 64, 192, 1000, "bf16", "lm")
-    p = ModelDesc("prm", 1, 192, 3, 1, 64, 320, 1000, "bf16", "prm")
-    wl = Workload("gen_mfma", t, d, p, B=2, n=5, L=19, prefix_len=0, lens_range=(40, 300), betas=(1.0,),
-                  token_dist="zipf", page_tokens=16, seed=14, u_seed=12)
+    wl = mfma_workload()
     step = synthetic.ScoringStep(wl)
     step.prefill()
     u = W.rng.uniform_f64(wl.u_seed, "gen/u4", wl.B * wl.n * wl.L).reshape(wl.B, wl.n, wl.L)

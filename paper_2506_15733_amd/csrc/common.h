@@ -59,8 +59,8 @@ void launch_rmsnorm_shifted(const float* x, const float* h_last, const float* ga
 void launch_rope_table(float* cs, const BatchGeom& g, int hd, float base, hipStream_t s);
 // values leave this kernel transposed per candidate: vT[cand][Hkv][hd][Lp], Lp = L rounded up to 16
 template <typename T>
-void launch_rope_split(const float* qkv, const float* cs, T* q, T* k, T* vT, const BatchGeom& g, int Lp,
-                       const ModelDims& md, hipStream_t s);
+void launch_rope_split(const float* qkv, int parts, const float* cs, T* q, T* k, T* vT, const BatchGeom& g, int Lp,
+                       const ModelDims& md, hipStream_t s);   // qkv = sum of `parts` slices [M, (Hq+2Hkv)*hd]
 template <typename T>
 void launch_transpose_v(const T* v, T* vT, int cands, int Hkv, int hd, int L, int Lp, hipStream_t s);
 template <typename T>
@@ -127,3 +127,8 @@ template <typename T>
 void launch_add_partials_rmsnorm(float* x, const float* P, int parts, int init, const float* gain, T* out, int M, int d,
                                  float eps, hipStream_t s);
 int mfma_lmhead_tiles(int V);
+// Weight-streaming GEMM for M <= 32 rows (gemm_skinny.hip): MFMA_STORE writes ksplit partial products
+// [ksplit][M][N]; MFMA_SWIGLU (ksplit 1) writes silu(gate)*up. Returns false if the shape is not taken.
+bool launch_gemm_skinny(int epi, const bf16_t* A, const bf16_t* W, int M, int N, int K, float* C, bf16_t* act,
+                        int ksplit, hipStream_t s);
+int skinny_gemm_split(int N, int K, int max_split);

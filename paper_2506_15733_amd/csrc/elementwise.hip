@@ -216,7 +216,7 @@ void launch_rope_table(float* cs, const BatchGeom& g, int hd, float base, hipStr
 template <typename T>
 __global__ void rope_split_kernel(const float* __restrict__ qkv, const float* __restrict__ cs, T* __restrict__ q,
                                   T* __restrict__ kblk, T* __restrict__ vT, int Hq, int Hkv, int hd, int Lrows, int t0,
-                                  int L, int Lp) {
+                                  int L, int Lp, int parts, size_t part_stride) {
   size_t m = blockIdx.x;
   int H = Hq + 2 * Hkv, half = hd / 2;
   const float* in = qkv + m * (size_t)H * hd;
@@ -227,6 +227,10 @@ __global__ void rope_split_kernel(const float* __restrict__ qkv, const float* __
   for (int e = threadIdx.x; e < H * half; e += blockDim.x) {
     int h = e / half, i = e % half;
     float x1 = in[h * hd + i], x2 = in[h * hd + half + i];
+    for (int pidx = 1; pidx < parts; ++pidx) {           // K-split projection: add the slices up, in order
+      x1 += in[pidx * part_stride + h * hd + i];
+      x2 += in[pidx * part_stride + h * hd + half + i];
+    }
     if (h < Hq + Hkv) {
       float cn = c[i], sn = c[half + i];
       float y1 = x1 * cn - x2 * sn, y2 = x2 * cn + x1 * sn;
@@ -245,14 +249,15 @@ __global__ void rope_split_kernel(const float* __restrict__ qkv, const float* __
   }
 }
 template <typename T>
-void launch_rope_split(const float* qkv, const float* cs, T* q, T* k, T* vT, const BatchGeom& g, int Lp,
+void launch_rope_split(const float* qkv, int parts, const float* cs, T* q, T* k, T* vT, const BatchGeom& g, int Lp,
                        const ModelDims& md, hipStream_t s) {
-  rope_split_kernel<T><<<g.M, 256, 0, s>>>(qkv, cs, q, k, vT, md.Hq, md.Hkv, md.hd, g.L, g.t0, g.Lk, Lp);
+  size_t stride = (size_t)g.M * (md.Hq + 2 * md.Hkv) * md.hd;
+  rope_split_kernel<T><<<g.M, 256, 0, s>>>(qkv, cs, q, k, vT, md.Hq, md.Hkv, md.hd, g.L, g.t0, g.Lk, Lp, parts, stride);
 }
-template void launch_rope_split<float>(const float*, const float*, float*, float*, float*, const BatchGeom&, int,
+template void launch_rope_split<float>(const float*, int, const float*, float*, float*, float*, const BatchGeom&, int,
                                        const ModelDims&, hipStream_t);
-template void launch_rope_split<bf16_t>(const float*, const float*, bf16_t*, bf16_t*, bf16_t*, const BatchGeom&, int,
-                                        const ModelDims&, hipStream_t);
+template void launch_rope_split<bf16_t>(const float*, int, const float*, bf16_t*, bf16_t*, bf16_t*, const BatchGeom&,
+                                        int, const ModelDims&, hipStream_t);
 
 // v [M][Hkv][hd] -> vT [cand][Hkv][hd][Lp], zero padded (used when values arrive in token-major order)
 template <typename T>

@@ -310,6 +310,10 @@ static int gemm_residual_split(const T* A, const T* W, float* x, float* part, in
 template <>
 int gemm_residual_split<bf16_t>(const bf16_t* A, const bf16_t* W, float* x, float* part, int max_split, int M, int N,
                                 int K, hipStream_t s) {
+  if (M <= 32 && max_split >= 1) {                       // a few rows: stream the weights once, K in slices
+    int sp = skinny_gemm_split(N, K, max_split);
+    if (launch_gemm_skinny(MFMA_STORE, A, W, M, N, K, part, nullptr, sp, s)) return sp;
+  }
   int bm = 0, split = 1;
   if (K % 64 == 0 && max_split > 1) mfma_gemm_plan(M, N, K, max_split, &bm, &split);
   if (split > 1 &&
@@ -317,6 +321,23 @@ int gemm_residual_split<bf16_t>(const bf16_t* A, const bf16_t* W, float* x, floa
     return split;
   gemm<bf16_t>(A, W, x, M, N, K, EPI_RESIDUAL_ADD, s);
   return 0;
+}
+
+// C = A W^T as up to max_split K slices [slices][M][N] that the consumer adds up; returns their number.
+template <typename T>
+static int gemm_store_split(const T* A, const T* W, float* C, int max_split, int M, int N, int K, hipStream_t s) {
+  gemm<T>(A, W, C, M, N, K, EPI_STORE_F32, s);
+  return 1;
+}
+template <>
+int gemm_store_split<bf16_t>(const bf16_t* A, const bf16_t* W, float* C, int max_split, int M, int N, int K,
+                             hipStream_t s) {
+  if (M <= 32 && max_split >= 1) {
+    int sp = skinny_gemm_split(N, K, max_split);
+    if (launch_gemm_skinny(MFMA_STORE, A, W, M, N, K, C, nullptr, sp, s)) return sp;
+  }
+  gemm<bf16_t>(A, W, C, M, N, K, EPI_STORE_F32, s);
+  return 1;
 }
 
 // act[M,F] = silu(A Wg^T) * (A Wu^T) with Wgu interleaved by 32 rows
@@ -327,6 +348,7 @@ static void gate_up(const T* A, const T* Wgu, float* gu, T* act, int M, int F, i
 }
 template <>
 void gate_up<bf16_t>(const bf16_t* A, const bf16_t* Wgu, float* gu, bf16_t* act, int M, int F, int K, hipStream_t s) {
+  if (M <= 32 && launch_gemm_skinny(MFMA_SWIGLU, A, Wgu, M, 2 * F, K, nullptr, act, 1, s)) return;
   if (launch_gemm_mfma(MFMA_SWIGLU, A, Wgu, M, 2 * F, K, nullptr, act, nullptr, nullptr, nullptr, nullptr, 1, 0, s)) return;
   launch_gemm_simple<bf16_t>(A, Wgu, gu, M, 2 * F, K, EPI_STORE_F32, s);
   launch_silu_mul<bf16_t>(gu, act, M, F, s);
@@ -380,9 +402,11 @@ static void run_trunk(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
     T* pK = pool_ptr<T>(p, d, l, 0);
     T* pV = pool_ptr<T>(p, d, l, 1);
     if (!normed) PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(x, L.g_attn, (T*)ws.a, g.M, md.d, md.eps, s));
+    int qkv_parts = 1;                                   // ws.qkv has room for R / g.M slices of the projection
     PROFILED(ctx, SPECS_K_QKV, s,
-             gemm<T>((const T*)ws.a, (const T*)L.wqkv, ws.qkv, g.M, qd + 2 * kvd, md.d, EPI_STORE_F32, s));
-    PROFILED(ctx, SPECS_K_OTHER, s, launch_rope_split<T>(ws.qkv, ws.cs, (T*)ws.q, kb, vb, g, Lp, md, s));
+             qkv_parts = gemm_store_split<T>((const T*)ws.a, (const T*)L.wqkv, ws.qkv, (int)(R / g.M < 8 ? R / g.M : 8),
+                                             g.M, qd + 2 * kvd, md.d, s));
+    PROFILED(ctx, SPECS_K_OTHER, s, launch_rope_split<T>(ws.qkv, qkv_parts, ws.cs, (T*)ws.q, kb, vb, g, Lp, md, s));
     PROFILED(ctx, SPECS_K_ATTENTION, s,
              attention<T>((const T*)ws.q, kb, vb, pK, pV, (T*)ws.attn, g, md, Lp, max_ctx, ws.gu,
                           (size_t)R * 2 * md.F, s));
@@ -481,7 +505,7 @@ static int generate_impl(specs_ctx* ctx, const specs_model* m, const specs_prefi
     g.t0 = t;
     PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(ws.xs, m->w.g_final, (T*)ws.a, g.M, d.d_model, d.rms_eps, s));
     PROFILED(ctx, SPECS_K_LMHEAD, s,
-             gemm<T>((const T*)ws.a, (const T*)m->w.head, ws.logits, g.M, d.vocab, d.d_model, EPI_STORE_F32, s));
+             gemm_store_split<T>((const T*)ws.a, (const T*)m->w.head, ws.logits, 1, g.M, d.vocab, d.d_model, s));
     PROFILED(ctx, SPECS_K_OTHER, s,
              launch_sample_tokens(ws.logits, g.M, d.vocab, limit, u, cand, tl, L, t, ws.status, s));
     run_trunk<T>(ctx, m, p, ws, g, ws.xs, cand + t, L, max_ctx, false, R, C, s);
@@ -616,7 +640,12 @@ extern "C" int specs_op_linear(specs_ctx* ctx, int32_t dtype, const void* A, con
     int bm = 0, split = 1;
     if (K % 64 == 0 && room > 1) mfma_gemm_plan(M, N, K, room > 8 ? 8 : (int)room, &bm, &split);
     float* part = (float*)(ctx->workspace + 256);
-    if (split > 1 && launch_gemm_mfma(MFMA_STORE, (const bf16_t*)A, (const bf16_t*)W, M, N, K, part, nullptr, nullptr,
+    int sk = M <= 32 && room >= 1 ? skinny_gemm_split(N, K, room > 8 ? 8 : (int)room) : 0;
+    if (sk && launch_gemm_skinny(MFMA_STORE, (const bf16_t*)A, (const bf16_t*)W, M, N, K, part, nullptr, sk,
+                                 ctx->stream)) {
+      launch_add_partials_rmsnorm<bf16_t>(C, part, sk, accumulate ? 0 : 1, nullptr, nullptr, M, N, 0.f, ctx->stream);
+      ctx->last_model = nullptr;
+    } else if (split > 1 && launch_gemm_mfma(MFMA_STORE, (const bf16_t*)A, (const bf16_t*)W, M, N, K, part, nullptr, nullptr,
                                       nullptr, nullptr, nullptr, split, bm, ctx->stream)) {
       launch_add_partials_rmsnorm<bf16_t>(C, part, split, accumulate ? 0 : 1, nullptr, nullptr, M, N, 0.f, ctx->stream);
       ctx->last_model = nullptr;                         // the workspace no longer holds a scored block

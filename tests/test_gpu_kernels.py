@@ -37,7 +37,9 @@ def close(got, want, rel):
 
 LINEAR_SHAPES = [(45, 100, 64), (256, 256, 64), (300, 1152, 128), (130, 257, 192), (300, 1152, 256), (130, 257, 320),
                  (77, 2100, 448), (2048, 4608, 3584),
-                 (1024, 1536, 8960), (256, 1024, 2816), (2048, 3584, 18944)]
+                 (1024, 1536, 8960), (256, 1024, 2816), (2048, 3584, 18944),
+                 # a few rows (one position of every candidate during generation): the weight-streaming kernel
+                 (16, 4608, 3584), (16, 3584, 18944), (5, 301, 128), (32, 2050, 1280), (17, 1536, 8960), (1, 64, 256)]
 
 
 @pytest.mark.parametrize("M,N,K", LINEAR_SHAPES)
@@ -67,7 +69,8 @@ def test_linear_f32(ctx):
     close(out.cpu().numpy().astype(np.float64), oracle.linear(a, w), 2e-6)
 
 
-@pytest.mark.parametrize("M,F,K", [(45, 96, 64), (300, 160, 128), (300, 1120, 256), (256, 2816, 1024), (2048, 18944, 3584)])
+@pytest.mark.parametrize("M,F,K", [(45, 96, 64), (300, 160, 128), (300, 1120, 256), (256, 2816, 1024), (2048, 18944, 3584),
+                                   (16, 18944, 3584), (7, 96, 128), (32, 8960, 1536), (19, 160, 384)])
 def test_gate_up_bf16(ctx, M, F, K):
     from paper_2506_15733_amd import binding as B
     from paper_2506_15733_amd.synthetic import pack_gate_up

@@ -347,7 +347,8 @@ bool launch_attention_mfma_decode_prefix(const bf16_t* q, const bf16_t* poolK, c
   a.q_tiles = (rows + 127) / 128;
   int base = g.B * md.Hkv * a.q_tiles;
   int max_tiles = (max_ctx + 63) / 64;
-  int splits = (512 + base - 1) / base;                 // about two workgroups per CU
+  int splits = (512 + base - 1) / base;                 // about two workgroups per CU ...
+  splits = splits > 16 ? 16 : splits;                   // ... but few enough partial results for the merge to stay cheap
   splits = splits > max_tiles ? max_tiles : splits;
   splits = splits < 1 ? 1 : splits;
   size_t per_split = (size_t)base * 128 * (md.hd + 2);

@@ -80,8 +80,10 @@ void launch_scatter_last_rows(const float* xs, float* x, int C, int L, int d, hi
 void launch_block_sum(const float* tok_logp, float* block_out, int L, int C, hipStream_t s);
 // Ancestral sampling of one token per row from softmax(logits[row, :limit]) by inverse CDF in id order from the
 // uniform u[row*L + t]; writes the id to cand[row*L + t] and its log-probability to tok_logp[row*L + t].
+// scratch: sample_scratch_bytes(rows) bytes, 8-byte aligned.
 void launch_sample_tokens(const float* logits, int rows, int V, int limit, const double* u, int32_t* cand,
-                          float* tok_logp, int L, int t, int* status, hipStream_t s);
+                          float* tok_logp, int L, int t, void* scratch, int* status, hipStream_t s);
+size_t sample_scratch_bytes(int rows);
 
 enum GemmEpilogue { EPI_STORE_F32 = 0, EPI_RESIDUAL_ADD = 1 };
 // C[M,N] (float) = A[M,K] * W[N,K]^T, or C += ... (residual add)

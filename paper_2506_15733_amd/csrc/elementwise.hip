@@ -224,26 +224,30 @@ __global__ void rope_split_kernel(const float* __restrict__ qkv, const float* __
   size_t cand = m / Lrows;
   int t = t0 + (int)(m % Lrows);
   const size_t krow = cand * L + t;
-  for (int e = threadIdx.x; e < H * half; e += blockDim.x) {
-    int h = e / half, i = e % half;
-    float x1 = in[h * hd + i], x2 = in[h * hd + half + i];
-    for (int pidx = 1; pidx < parts; ++pidx) {           // K-split projection: add the slices up, in order
-      x1 += in[pidx * part_stride + h * hd + i];
-      x2 += in[pidx * part_stride + h * hd + half + i];
-    }
-    if (h < Hq + Hkv) {
-      float cn = c[i], sn = c[half + i];
-      float y1 = x1 * cn - x2 * sn, y2 = x2 * cn + x1 * sn;
-      T* o = (h < Hq) ? q + (m * Hq + h) * hd : kblk + (krow * Hkv + (h - Hq)) * hd;
-      o[i] = from_f32<T>(y1);
-      o[half + i] = from_f32<T>(y2);
-    } else {
-      T* o = vT + ((cand * Hkv + (h - Hq - Hkv)) * hd) * Lp + t;
-      o[(size_t)i * Lp] = from_f32<T>(x1);
-      o[(size_t)(half + i) * Lp] = from_f32<T>(x2);
+  // blockIdx.y strides over the heads (one block per row when gridDim.y == 1, one per (row, head) for few rows)
+  const int heads_here = (H - (int)blockIdx.y + (int)gridDim.y - 1) / (int)gridDim.y;
+  {
+    for (int e = threadIdx.x; e < heads_here * half; e += blockDim.x) {
+      const int h = blockIdx.y + (e / half) * gridDim.y, i = e % half;
+      float x1 = in[h * hd + i], x2 = in[h * hd + half + i];
+      for (int pidx = 1; pidx < parts; ++pidx) {         // K-split projection: add the slices up, in order
+        x1 += in[pidx * part_stride + h * hd + i];
+        x2 += in[pidx * part_stride + h * hd + half + i];
+      }
+      if (h < Hq + Hkv) {
+        float cn = c[i], sn = c[half + i];
+        float y1 = x1 * cn - x2 * sn, y2 = x2 * cn + x1 * sn;
+        T* o = (h < Hq) ? q + (m * Hq + h) * hd : kblk + (krow * Hkv + (h - Hq)) * hd;
+        o[i] = from_f32<T>(y1);
+        o[half + i] = from_f32<T>(y2);
+      } else {
+        T* o = vT + ((cand * Hkv + (h - Hq - Hkv)) * hd) * Lp + t;
+        o[(size_t)i * Lp] = from_f32<T>(x1);
+        o[(size_t)(half + i) * Lp] = from_f32<T>(x2);
+      }
     }
   }
-  if (t == L - 1 && Lp > L) {
+  if (blockIdx.y == 0 && t == L - 1 && Lp > L) {
     for (int e = threadIdx.x; e < Hkv * hd; e += blockDim.x)
       for (int tt = L; tt < Lp; ++tt) vT[(cand * Hkv * hd + e) * Lp + tt] = from_f32<T>(0.f);
   }
@@ -252,7 +256,11 @@ template <typename T>
 void launch_rope_split(const float* qkv, int parts, const float* cs, T* q, T* k, T* vT, const BatchGeom& g, int Lp,
                        const ModelDims& md, hipStream_t s) {
   size_t stride = (size_t)g.M * (md.Hq + 2 * md.Hkv) * md.hd;
-  rope_split_kernel<T><<<g.M, 256, 0, s>>>(qkv, cs, q, k, vT, md.Hq, md.Hkv, md.hd, g.L, g.t0, g.Lk, Lp, parts, stride);
+  if (g.M <= 64)       // few rows: spread the heads over blocks of one wavefront
+    rope_split_kernel<T><<<dim3(g.M, md.Hq + 2 * md.Hkv), 64, 0, s>>>(qkv, cs, q, k, vT, md.Hq, md.Hkv, md.hd, g.L, g.t0,
+                                                                     g.Lk, Lp, parts, stride);
+  else
+    rope_split_kernel<T><<<g.M, 256, 0, s>>>(qkv, cs, q, k, vT, md.Hq, md.Hkv, md.hd, g.L, g.t0, g.Lk, Lp, parts, stride);
 }
 template void launch_rope_split<float>(const float*, int, const float*, float*, float*, float*, const BatchGeom&, int,
                                        const ModelDims&, hipStream_t);

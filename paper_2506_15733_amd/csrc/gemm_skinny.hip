@@ -5,13 +5,13 @@
 //     straight into registers (64 contiguous bytes per row and instruction), the next slab requested before the
 //     current one is multiplied;
 //   * the weight rows are the A operand of v_mfma_f32_16x16x32_bf16, the (few) activation rows its B operand,
-//     read from an LDS copy of A that the workgroup's eight wavefronts share (staged 1024 columns at a time,
+//     read from an LDS copy of A that the workgroup's four or eight wavefronts share (staged 1024 columns at a time,
 //     16-byte chunks XOR-swizzled by the token index so that the 16 tokens of a read hit distinct banks);
 //   * K is cut into gridDim.y slices so that short N still yields a few thousand wavefronts; slice s writes its
 //     partial product to C + s*M*N and the consumer adds the slices up.
-// Epilogues: float store (partial products, or the result itself with one slice), or SwiGLU: the wavefront then
-// owns 16 gate rows and the 16 up rows of the same units (the fused gate/up matrix interleaves them in groups of
-// 32 rows) and writes silu(gate) * up as bf16.
+// Epilogues: float store (partial products, or the result itself with one slice), or SwiGLU: the wavefront's 16
+// rows are then the gate rows and the up rows of the same 8 units (the fused gate/up matrix interleaves them in
+// groups of 32 rows) and it writes silu(gate) * up as bf16.
 #include "common.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -28,21 +28,23 @@ struct SkinnyArgs {
   int M, N, K, ksplit;
 };
 
-template <int TG, int EPI>
-__global__ void __launch_bounds__(512) gemm_skinny_kernel(SkinnyArgs a) {
+template <int TG, int EPI, int WPB>
+__global__ void __launch_bounds__(64 * WPB) gemm_skinny_kernel(SkinnyArgs a) {
   constexpr int STAGE_COLS = 1024;                       // activation columns resident in LDS
   constexpr int ROWB = STAGE_COLS * 2;                   // bytes per LDS row
-  constexpr int NSUB = EPI == SK_SWIGLU ? 2 : 1;         // weight-row sets per wavefront
+  constexpr int NSUB = 1;                                // weight-row sets per wavefront
   __shared__ __attribute__((aligned(16))) char As[16 * TG * ROWB];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, c = lane >> 4;
-  const int wt = blockIdx.x * 8 + wave;                  // 16-row (SwiGLU: 16-unit) tile of this wavefront
+  const int wt = blockIdx.x * WPB + wave;                  // 16-row (SwiGLU: 16-unit) tile of this wavefront
   int wrow[NSUB];
   bool live;
   if (EPI == SK_SWIGLU) {
-    wrow[0] = 64 * (wt >> 1) + 16 * (wt & 1) + r;        // gate rows; up rows are 32 further
-    wrow[NSUB - 1] = wrow[0] + 32;
-    live = 64 * (wt >> 1) < a.N;
+    // A-operand rows 0..7: the gate rows of units 8*wt .. 8*wt+7, rows 8..15: their up rows (the fused matrix keeps
+    // the gate rows of units 32Q..32Q+31 at 64Q.., their up rows 32 further)
+    const int unit = 8 * wt + (r & 7);
+    wrow[0] = 64 * (unit >> 5) + (unit & 31) + (r >> 3) * 32;
+    live = 16 * wt < a.N;
   } else {
     wrow[0] = wt * 16 + r;
     live = wt * 16 < a.N;
@@ -62,7 +64,11 @@ __global__ void __launch_bounds__(512) gemm_skinny_kernel(SkinnyArgs a) {
 #pragma unroll
     for (int g = 0; g < TG; ++g) acc[u][g] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  bf16x8 wcur[NSUB][4], wnext[NSUB][4];
+  // PF register sets take turns: while one slab is multiplied the loads of the next PF-1 are in flight, which is
+  // what keeps HBM busy when a launch has only a few wavefronts per CU
+  constexpr int PF = 2;
+  static_assert((STAGE_COLS / 128) % PF == 0, "a stage must hold a whole number of register-set rounds");
+  bf16x8 w[PF][NSUB][4];
   auto load_slab = [&](int kt, bf16x8 (&dst)[NSUB][4]) {
     const int ktc = kt < kt1 ? kt : kt1 - 1;             // past the end: a redundant in-bounds load, never used
 #pragma unroll
@@ -70,39 +76,47 @@ __global__ void __launch_bounds__(512) gemm_skinny_kernel(SkinnyArgs a) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) dst[u][j] = *(const bf16x8*)(wp[u] + (size_t)ktc * 128 + 32 * j);
   };
-  if (kt0 < kt1) load_slab(kt0, wcur);
-
-  for (int s0 = kt0; s0 < kt1; s0 += STAGE_COLS / 128) {
-    const int s1 = s0 + STAGE_COLS / 128 < kt1 ? s0 + STAGE_COLS / 128 : kt1;
-    __syncthreads();                                     // everybody is done with the previous stage
-    // stage A[:, s0*128 .. s1*128): 16-byte chunk ch of token row m goes to chunk position ch ^ (m & 15)
-    const int chunks_per_row = (s1 - s0) * 16;
-    for (int q = tid; q < 16 * TG * chunks_per_row; q += 512) {
-      int m = q / chunks_per_row, ch = q - m * chunks_per_row;
-      bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (m < a.M) v = *(const bf16x8*)(a.A + (size_t)m * a.K + (size_t)s0 * 128 + ch * 8);
-      *(bf16x8*)(As + m * ROWB + ((ch ^ (m & 15)) << 4)) = v;
-    }
-    __syncthreads();
-    for (int kt = s0; kt < s1; ++kt) {
-      load_slab(kt + 1, wnext);
-      const int chbase = (kt - s0) * 16 + c;             // chunk of this lane's k-offset 8c within the slab, + 4j below
+  auto multiply = [&](int slab_in_stage, const bf16x8 (&w)[NSUB][4]) {
+    const int chbase = slab_in_stage * 16 + c;           // chunk of this lane's k-offset 8c within the slab, + 4j below
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < 4; ++j) {
 #pragma unroll
-        for (int g = 0; g < TG; ++g) {
-          const int m = g * 16 + r;
-          bf16x8 bv = *(const bf16x8*)(As + m * ROWB + (((chbase + 4 * j) ^ r) << 4));
+      for (int g = 0; g < TG; ++g) {
+        const int m = g * 16 + r;
+        bf16x8 bv = *(const bf16x8*)(As + m * ROWB + (((chbase + 4 * j) ^ r) << 4));
 #pragma unroll
-          for (int u = 0; u < NSUB; ++u)
-            acc[u][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wcur[u][j], bv, acc[u][g], 0, 0, 0);
-        }
+        for (int u = 0; u < NSUB; ++u)
+          acc[u][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[u][j], bv, acc[u][g], 0, 0, 0);
       }
-#pragma unroll
-      for (int u = 0; u < NSUB; ++u)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) wcur[u][j] = wnext[u][j];
     }
+  };
+#pragma unroll
+  for (int i = 0; i < PF - 1; ++i) load_slab(kt0 + i, w[i]);
+  int kt = kt0, s0 = kt0;
+  while (kt < kt1) {
+    if (((kt - kt0) & (STAGE_COLS / 128 - 1)) == 0) {
+      s0 = kt;
+      const int s1 = s0 + STAGE_COLS / 128 < kt1 ? s0 + STAGE_COLS / 128 : kt1;
+      __syncthreads();                                   // everybody is done with the previous stage
+      // stage A[:, s0*128 .. s1*128): 16-byte chunk ch of token row m goes to chunk position ch ^ (m & 15)
+      const int chunks_per_row = (s1 - s0) * 16;
+      for (int q = tid; q < 16 * TG * chunks_per_row; q += 64 * WPB) {
+        int m = q / chunks_per_row, ch = q - m * chunks_per_row;
+        bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (m < a.M) v = *(const bf16x8*)(a.A + (size_t)m * a.K + (size_t)s0 * 128 + ch * 8);
+        *(bf16x8*)(As + m * ROWB + ((ch ^ (m & 15)) << 4)) = v;
+      }
+      __syncthreads();
+    }
+    // one round: slab kt + i is in set i; set (i + PF - 1) % PF is refilled with slab kt + i + PF - 1
+#pragma unroll
+    for (int i = 0; i < PF; ++i) {
+      if (kt + i < kt1) {
+        load_slab(kt + i + PF - 1, w[(i + PF - 1) % PF]);
+        multiply(kt + i - s0, w[i]);
+      }
+    }
+    kt += PF;
   }
   if (!live) return;
   // accumulator element e of this lane: weight row 4c + e of the tile, token r (+ 16 per token group)
@@ -123,19 +137,22 @@ __global__ void __launch_bounds__(512) gemm_skinny_kernel(SkinnyArgs a) {
       }
     }
   } else {
+    // lanes c = 0, 1 hold the gate values of units 4c + e, lanes c = 2, 3 (32 lanes further) the up values of the same
+    // units: one exchange across the half-wave pairs them
     const int F = a.N >> 1;
-    const int unit = 32 * (wt >> 1) + 16 * (wt & 1) + 4 * c;
+    const int unit = 8 * wt + 4 * (c & 1);
 #pragma unroll
     for (int g = 0; g < TG; ++g) {
       const int m = g * 16 + r;
-      if (m >= a.M) continue;
       bf16x4 o;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        float gt = acc[0][g][e], up = acc[NSUB - 1][g][e];
+        float mine = acc[0][g][e];
+        float other = __shfl_xor(mine, 32, 64);
+        float gt = c < 2 ? mine : other, up = c < 2 ? other : mine;
         o[e] = (__bf16)(gt * __frcp_rn(1.0f + __expf(-gt)) * up);
       }
-      *(bf16x4*)(a.act + (size_t)m * F + unit) = o;
+      if (c < 2 && m < a.M) *(bf16x4*)(a.act + (size_t)m * F + unit) = o;
     }
   }
 }
@@ -162,14 +179,18 @@ bool launch_gemm_skinny(int epi, const bf16_t* A, const bf16_t* W, int M, int N,
   if (epi == MFMA_STORE && ((uintptr_t)C & 15)) return false;
   SkinnyArgs a;
   a.A = A; a.W = W; a.C = C; a.act = act; a.M = M; a.N = N; a.K = K; a.ksplit = ksplit;
-  int tiles = epi == MFMA_SWIGLU ? N / 32 : (N + 15) / 16;       // wavefront tiles
-  dim3 grid((tiles + 7) / 8, ksplit);
+  int tiles = (N + 15) / 16;                                     // wavefront tiles (SwiGLU: 8 units = 16 rows each)
+  // eight wavefronts share one LDS copy of A where that still leaves two workgroups per CU, else four
+  bool wide = (long)((tiles + 7) / 8) * ksplit >= 512;
+  dim3 grid(wide ? (tiles + 7) / 8 : (tiles + 3) / 4, ksplit);
+#define SKINNY(TG, E)                                                                  \
+  if (wide) gemm_skinny_kernel<TG, E, 8><<<grid, 512, 0, s>>>(a);                      \
+  else gemm_skinny_kernel<TG, E, 4><<<grid, 256, 0, s>>>(a)
   if (epi == MFMA_SWIGLU) {
-    if (M <= 16) gemm_skinny_kernel<1, SK_SWIGLU><<<grid, 512, 0, s>>>(a);
-    else gemm_skinny_kernel<2, SK_SWIGLU><<<grid, 512, 0, s>>>(a);
+    if (M <= 16) { SKINNY(1, SK_SWIGLU); } else { SKINNY(2, SK_SWIGLU); }
   } else {
-    if (M <= 16) gemm_skinny_kernel<1, SK_STORE><<<grid, 512, 0, s>>>(a);
-    else gemm_skinny_kernel<2, SK_STORE><<<grid, 512, 0, s>>>(a);
+    if (M <= 16) { SKINNY(1, SK_STORE); } else { SKINNY(2, SK_STORE); }
   }
+#undef SKINNY
   return true;
 }

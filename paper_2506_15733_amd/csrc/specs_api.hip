@@ -55,6 +55,7 @@ struct Workspace {
   int32_t* chosen;   // [B]
   float* xs;         // [C, d] residual stream of the one position a generation step processes (LM heads)
   float* logits;     // [C, V] next-token logits of a generation step (LM heads)
+  char* sample;      // per-chunk softmax statistics of the sampling kernels (LM heads)
   size_t total;
 };
 
@@ -88,6 +89,7 @@ static Workspace carve(char* base, const specs_model_desc& d, int64_t R, int64_t
   bool lm = d.head == SPECS_HEAD_LM;
   w.xs = (float*)take(lm ? (size_t)C * d.d_model * 4 : 0);
   w.logits = (float*)take(lm ? (size_t)C * d.vocab * 4 : 0);
+  w.sample = take(lm ? sample_scratch_bytes((int)C) : 0);
   w.total = off;
   return w;
 }
@@ -507,7 +509,7 @@ static int generate_impl(specs_ctx* ctx, const specs_model* m, const specs_prefi
     PROFILED(ctx, SPECS_K_LMHEAD, s,
              gemm_store_split<T>((const T*)ws.a, (const T*)m->w.head, ws.logits, 1, g.M, d.vocab, d.d_model, s));
     PROFILED(ctx, SPECS_K_OTHER, s,
-             launch_sample_tokens(ws.logits, g.M, d.vocab, limit, u, cand, tl, L, t, ws.status, s));
+             launch_sample_tokens(ws.logits, g.M, d.vocab, limit, u, cand, tl, L, t, ws.sample, ws.status, s));
     run_trunk<T>(ctx, m, p, ws, g, ws.xs, cand + t, L, max_ctx, false, R, C, s);
   }
   launch_scatter_last_rows(ws.xs, ws.x, (int)C, L, d.d_model, s);

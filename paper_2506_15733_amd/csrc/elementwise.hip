@@ -63,25 +63,45 @@ __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, float4 v) {
   *(bf16x4*)p = o;
 }
 
-template <typename T>
-__global__ void __launch_bounds__(256) norm_rows_vec_kernel(float* __restrict__ x, const float* __restrict__ P,
-                                                            int parts, int init, const float* __restrict__ gain,
-                                                            T* __restrict__ out, size_t Md, int d, float eps) {
-  __shared__ float red[4];
+template <int NW>
+__device__ __forceinline__ float block_sum_waves(float v, float* red) {   // NW wavefronts, red[NW]
+  v = wave_sum(v);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float t = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) t += red[w];
+  __syncthreads();
+  return t;
+}
+
+// NT threads per row: 256 for many rows, 1024 for a few (one 16-byte column per thread, and the loads of the
+// partial products of a column are issued four at a time so that their latencies overlap).
+template <typename T, int NT>
+__global__ void __launch_bounds__(NT) norm_rows_vec_kernel(float* __restrict__ x, const float* __restrict__ P,
+                                                           int parts, int init, const float* __restrict__ gain,
+                                                           T* __restrict__ out, size_t Md, int d, float eps) {
+  constexpr int VPT = 1024 / NT;
+  __shared__ float red[NT / 64];
   const size_t m = blockIdx.x;
   const int nv = d >> 2;
   float4* xr = (float4*)(x + m * d);
-  float4 v[4];
+  float4 v[VPT];
   float ss = 0.f;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int c = threadIdx.x + i * 256;
+  for (int i = 0; i < VPT; ++i) {
+    int c = threadIdx.x + i * NT;
     if (c < nv) {
       if (parts > 0) {
-        float4 acc = ((const float4*)(P + m * d))[c];
-        for (int sidx = 1; sidx < parts; ++sidx) {
-          float4 q = ((const float4*)(P + sidx * Md + m * d))[c];
-          acc.x += q.x; acc.y += q.y; acc.z += q.z; acc.w += q.w;
+        const float4* pc = (const float4*)(P + m * d) + c;
+        const size_t stride4 = Md >> 2;
+        float4 acc = pc[0];
+        for (int s0 = 1; s0 < parts; s0 += 4) {          // slices are added in order, loaded four at a time
+          float4 q[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) q[k] = s0 + k < parts ? pc[(size_t)(s0 + k) * stride4] : float4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int k = 0; k < 4; ++k) { acc.x += q[k].x; acc.y += q[k].y; acc.z += q[k].z; acc.w += q[k].w; }
         }
         if (!init) {
           float4 o = xr[c];
@@ -96,17 +116,23 @@ __global__ void __launch_bounds__(256) norm_rows_vec_kernel(float* __restrict__ 
     }
   }
   if (gain == nullptr) return;
-  ss = block_sum_256(ss, red);
+  ss = block_sum_waves<NT / 64>(ss, red);
   float inv = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int c = threadIdx.x + i * 256;
+  for (int i = 0; i < VPT; ++i) {
+    int c = threadIdx.x + i * NT;
     if (c < nv) {
       float4 gn = ((const float4*)gain)[c];
       float4 y = {v[i].x * inv * gn.x, v[i].y * inv * gn.y, v[i].z * inv * gn.z, v[i].w * inv * gn.w};
       store4<T>(out + m * d + 4 * c, y);
     }
   }
+}
+template <typename T>
+static void launch_norm_rows_vec(float* x, const float* P, int parts, int init, const float* gain, T* out, int M, int d,
+                                 float eps, hipStream_t s) {
+  if (M <= 64) norm_rows_vec_kernel<T, 1024><<<M, 1024, 0, s>>>(x, P, parts, init, gain, out, (size_t)M * d, d, eps);
+  else norm_rows_vec_kernel<T, 256><<<M, 256, 0, s>>>(x, P, parts, init, gain, out, (size_t)M * d, d, eps);
 }
 static inline bool vec_rows_ok(int d, const void* a, const void* b, const void* c, const void* e) {
   return d % 4 == 0 && d <= 4096 && (((uintptr_t)a | (uintptr_t)b | (uintptr_t)c | (uintptr_t)e) & 15) == 0;
@@ -122,7 +148,7 @@ __global__ void rmsnorm_kernel(const float* __restrict__ x, const float* __restr
 template <typename T>
 void launch_rmsnorm(const float* x, const float* gain, T* out, int M, int d, float eps, hipStream_t s) {
   if (vec_rows_ok(d, x, gain, out, nullptr))
-    norm_rows_vec_kernel<T><<<M, 256, 0, s>>>((float*)x, nullptr, 0, 0, gain, out, 0, d, eps);
+    launch_norm_rows_vec<T>((float*)x, nullptr, 0, 0, gain, out, M, d, eps, s);
   else
     rmsnorm_kernel<T><<<M, 256, 0, s>>>(x, gain, out, d, eps);
 }
@@ -157,7 +183,7 @@ template <typename T>
 void launch_add_partials_rmsnorm(float* x, const float* P, int parts, int init, const float* gain, T* out, int M, int d,
                                  float eps, hipStream_t s) {
   if (vec_rows_ok(d, x, P, gain, out))
-    norm_rows_vec_kernel<T><<<M, 256, 0, s>>>(x, P, parts, init, gain, out, (size_t)M * d, d, eps);
+    launch_norm_rows_vec<T>(x, P, parts, init, gain, out, M, d, eps, s);
   else
     add_partials_rmsnorm_kernel<T><<<M, 256, 0, s>>>(x, P, parts, init, gain, out, (size_t)M * d, d, eps);
 }

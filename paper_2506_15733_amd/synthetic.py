@@ -218,3 +218,96 @@ def run_specs_loop(step: ScoringStep, blocks, tau, beta_index=0, start_with_targ
         use_draft |= step.max_reward.cpu().numpy() > tau
     torch.cuda.synchronize()
     return np.array(chosen_all), np.array(gen_all), np.array(fast_all)
+
+
+def run_specs_generation_loop(step: ScoringStep, H, tau, beta_index=0, start_with_target=True):
+    """Alg. 1 end to end on the GPU for H iterations: Step I, the current generator of every beam (the target until
+    Step III switches the beam to the draft model, for good, once max_i r(Y_i|tr) > tau) draws n blocks of L tokens
+    with specs_generate_blocks; Step II, scores, SubSample and commit as in run_specs_loop. What has to run depends
+    on who generated:
+      all beams by the target: log pi_gen = log pi_target cancels in Eq. 1, only the PRM scores the candidates; the
+        target commits what it generated, the draft model runs over the one chosen block to keep its cache current;
+      all beams by the draft: its block log-likelihoods came out of the generation pass, so only target and PRM score;
+      mixed: both models generate for every beam, each beam keeps its generator's blocks, and all three models score.
+    Uniforms: stream "gen/u" [H, B, n, L] for the tokens, "loop/u" [H, B] for SubSample (seed wl.u_seed).
+    Returns (tokens [H, B, n, L], chosen [H, B], generator flags [H, B])."""
+    wl, dev = step.wl, step.device
+    Bn, n, L = wl.B, wl.n, wl.L
+    use_draft = np.zeros(Bn, dtype=bool) if start_with_target else np.ones(Bn, dtype=bool)
+    u_gen = W.rng.uniform_f64(wl.u_seed, "gen/u", H * Bn * n * L).reshape(H, Bn, n, L)
+    u_sel = W.rng.uniform_f64(wl.u_seed, "loop/u", H * Bn).reshape(H, Bn)
+    betas = (wl.betas[beta_index],)
+    limit = min(m.vocab for m in wl.models().values() if m.head == "lm")
+    f = lambda *s: torch.zeros(s, dtype=torch.float32, device=dev)
+    gen_cand = {r: torch.zeros((Bn, n, L), dtype=torch.int32, device=dev) for r in ("target", "draft")}
+    gen_logp = {r: f(Bn, n) for r in ("target", "draft")}
+    out1 = {r: f(Bn, 1) for r in ("target", "draft")}
+    tok1 = {r: f(Bn, 1, L) for r in ("target", "draft")}
+    zeros, idx = f(Bn, n), torch.zeros((Bn, 1), dtype=torch.int32, device=dev)
+    beams = torch.arange(Bn, device=dev)
+    tokens_all, chosen_all, gen_all = [], [], []
+
+    def generate(role, ud):
+        dm = step.models[role]
+        B.specs_generate_blocks(dm.ctx, dm.model, step.prefixes[role].handle, ud, gen_cand[role], gen_logp[role], None,
+                                limit)
+
+    def commit(role, which):
+        dm = step.models[role]
+        B.specs_commit_block(dm.ctx, dm.model, step.prefixes[role].handle, which)
+
+    for h in range(H):
+        ud = torch.from_numpy(u_gen[h]).to(dev)
+        us = torch.from_numpy(u_sel[h:h + 1].T.copy()).to(dev)
+        gens = sorted({"draft" if d else "target" for d in use_draft})
+        step._fork()
+        for r in gens:
+            generate(r, ud)
+        step._join()
+        if len(gens) == 1:
+            step.cand = gen_cand[gens[0]]
+        else:
+            step.cand = torch.where(torch.from_numpy(use_draft).to(dev)[:, None, None], gen_cand["draft"],
+                                    gen_cand["target"]).contiguous()
+        step._fork()
+        if gens == ["target"]:
+            step.score("prm")
+        elif gens == ["draft"]:
+            step.score("target")
+            step.score("prm")
+        else:
+            for r in step.ROLES:
+                step.score(r)
+        step._join()
+        if gens == ["target"]:
+            lt, lg = zeros, zeros
+        elif gens == ["draft"]:
+            lt, lg = step.out["target"], gen_logp["draft"]
+        else:
+            mask = torch.from_numpy(use_draft).to(dev)[:, None]
+            lt, lg = step.out["target"], torch.where(mask, step.out["draft"], step.out["target"]).contiguous()
+        B.specs_subsample(step.sel_ctx, lt, lg, step.out["prm"], betas, us, idx, None, step.max_reward)
+        torch.cuda.synchronize()
+        chosen = idx[:, 0].cpu().numpy()
+        tokens_all.append(step.cand.cpu().numpy().copy())
+        chosen_all.append(chosen.copy())
+        gen_all.append(use_draft.copy())
+        which = chosen.tolist()
+        step._fork()
+        if len(gens) == 1:
+            other = "draft" if gens[0] == "target" else "target"
+            commit(gens[0], which)                      # its workspace holds the blocks it generated
+            commit("prm", which)
+            if gens == ["draft"]:
+                commit("target", which)                 # the target scored all n candidates
+            else:                                       # the draft saw none of them: run it over the chosen block
+                picked = step.cand[beams, idx[:, 0].long()][:, None, :].contiguous()
+                step.score(other, cand=picked, out=out1[other], tok=tok1[other])
+                commit(other, [0] * Bn)
+        else:
+            for r in step.ROLES:
+                commit(r, which)
+        step._join()
+        use_draft |= step.max_reward.cpu().numpy() > tau
+    torch.cuda.synchronize()
+    return np.array(tokens_all), np.array(chosen_all), np.array(gen_all)

@@ -167,3 +167,46 @@ def test_generation_log_probs_equal_block_scoring_of_the_same_tokens_bf16_mfma_s
         assert np.abs(step.tok[role].cpu().numpy() - tok).max() < 2e-2
         assert np.abs(step.out[role].cpu().numpy() - logp).max() < 2e-2 * np.sqrt(wl.L)
     step.close()
+
+
+@pytest.mark.parametrize("beams,tau", [(1, 0.5), (3, 0.5), (1, 2.0)])
+def test_full_specs_iterations_with_gpu_generation_match_the_oracle(beams, tau):
+    """Alg. 1 end to end (generate, score, SubSample, commit, switch) on the GPU against the same loop written with
+    the oracle, float configuration: generated tokens, chosen indices and switching decisions must be identical.
+    tau = 2 never switches (the target generates throughout: PRM-only scoring); tau = 0.5 switches after the first
+    iteration; with three beams of different rewards the generators may differ between beams."""
+    from paper_2506_15733_amd import synthetic
+    wl = small_workload("f32", B=beams, n=3, L=4, seed=23)
+    H = 3
+    step = synthetic.ScoringStep(wl, extra_tokens=H * wl.L)
+    step.prefill()
+    tokens, chosen, gen = synthetic.run_specs_generation_loop(step, H, tau)
+    # the oracle's loop
+    models = wl.models()
+    hws = {r: HostWeights(models[r], wl.seed) for r in models}
+    traces = [p.copy() for p in wl.prefix_tokens()]
+    use_draft = np.zeros(wl.B, dtype=bool)
+    u_gen = W.rng.uniform_f64(wl.u_seed, "gen/u", H * wl.B * wl.n * wl.L).reshape(H, wl.B, wl.n, wl.L)
+    u_sel = W.rng.uniform_f64(wl.u_seed, "loop/u", H * wl.B).reshape(H, wl.B)
+    for h in range(H):
+        caches = {r: oracle.prefill(models[r], hws[r], traces) for r in models}
+        new_flags = use_draft.copy()
+        for b in range(wl.B):
+            g = "draft" if use_draft[b] else "target"
+            assert gen[h, b] == use_draft[b]
+            cand, _, lgen, _, _ = oracle.generate_blocks(models[g], hws[g], caches[g][b], wl.n, wl.L, u_gen[h, b])
+            assert np.array_equal(cand, tokens[h, b]), (h, b)
+            lt, _ = oracle.score_cached(models["target"], hws["target"], [caches["target"][b]], cand[None])
+            r = oracle.score_cached(models["prm"], hws["prm"], [caches["prm"][b]], cand[None])[0]
+            k = oracle.subsample(lt[0], lgen if use_draft[b] else lt[0], r, wl.betas[0], float(u_sel[h, b]))
+            assert chosen[h, b] == k, (h, b)
+            traces[b] = np.concatenate([traces[b], cand[k]])
+            new_flags[b] |= r.max() > tau
+        use_draft = new_flags
+    if tau < 1:
+        assert gen.any()
+    else:
+        assert not gen.any()
+    for r in ("target", "draft", "prm"):
+        assert step.prefixes[r].lens_dev.cpu().tolist() == [len(t) for t in traces]
+    step.close()

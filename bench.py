@@ -183,6 +183,31 @@ def generate_bench(args):
     print(json.dumps(line))
 
 
+def loop_bench(args):
+    """Whole iterations of Alg. 1 with the draft model as the generator (after the switch of Step III) and with the
+    target as the generator (before it): generation, scoring by the models still needed, SubSample, commit."""
+    import torch
+    import workload as W
+    from paper_2506_15733_amd import synthetic
+    wl = W.get_config(args.workload)
+    H = args.specs_loop
+    out = {"metric": "Alg. 1 iterations (generate n blocks, score, SubSample, commit) on 1 MI355X",
+           "config": {"workload": wl.name, "B": wl.B, "n": wl.n, "L": wl.L, "iterations": H}}
+    step = synthetic.ScoringStep(wl, device="cuda:0", extra_tokens=2 * (H + 1) * wl.L)
+    step.prefill()
+    torch.cuda.synchronize()
+    for name, start_with_target, tau in (("draft_generates", False, 2.0), ("target_generates", True, 2.0)):
+        synthetic.run_specs_generation_loop(step, 1, tau, start_with_target=start_with_target)     # warm-up iteration
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        synthetic.run_specs_generation_loop(step, H, tau, start_with_target=start_with_target)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / H
+        out[name] = {"ms_per_iteration": dt * 1e3, "accepted_tokens_per_s": wl.B * wl.L / dt,
+                     "candidate_tokens_per_s": wl.B * wl.n * wl.L / dt}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--kernel", default=None, help="gate_up|qkv|o|down|lmhead|attn|copy: time that kernel alone")
@@ -194,11 +219,15 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--serial", action="store_true", help="one stream for the three passes instead of one each")
     ap.add_argument("--generate", default=None, help="draft|target: time block generation (Alg. 1 Step I) by that model")
+    ap.add_argument("--specs-loop", type=int, default=0, metavar="H",
+                    help="time H full iterations of Alg. 1 (generate, score, SubSample, commit) per generator")
     args = ap.parse_args()
     if args.kernel:
         return kernel_bench(args)
     if args.generate:
         return generate_bench(args)
+    if args.specs_loop:
+        return loop_bench(args)
     if args.gpus != 1:
         print("bench.py measures the one-GPU share of the path; --gpus must be 1 (nothing here uses a second GPU)",
               file=sys.stderr)

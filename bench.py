@@ -77,7 +77,7 @@ def kernel_bench(args):
     wl = W.get_config(args.workload)
     d = wl.target
     dev = "cuda:0"
-    M = wl.B * wl.n * wl.L
+    M = args.rows if args.rows else wl.B * wl.n * wl.L     # --rows 16: one position of every candidate (generation)
     qd, kvd = d.n_q_heads * d.head_dim, d.n_kv_heads * d.head_dim
     ws = torch.zeros(3 << 30, dtype=torch.uint8, device=dev)
     ctx = B.specs_ctx_create(0, torch.cuda.current_stream().cuda_stream, ws)
@@ -129,8 +129,11 @@ def kernel_bench(args):
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / args.reps
-    print(json.dumps({"kernel": k, "workload": wl.name, "ms": ms, "tflops": flops / ms / 1e9,
-                      "frac_mfma_peak": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}))
+    line = {"kernel": k, "workload": wl.name, "rows": M, "ms": ms, "tflops": flops / ms / 1e9,
+            "frac_mfma_peak": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}
+    if k in ("gate_up", "qkv", "o", "down", "lmhead"):
+        line["weight_GBps"] = Wm.numel() * Wm.element_size() / ms / 1e6       # the binding figure for a few rows
+    print(json.dumps(line))
 
 
 def model_bytes(d):
@@ -212,6 +215,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--kernel", default=None, help="gate_up|qkv|o|down|lmhead|attn|copy: time that kernel alone")
     ap.add_argument("--reps", type=int, default=20)
+    ap.add_argument("--rows", type=int, default=0, help="with --kernel: activation rows (default: the workload's B*n*L)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)

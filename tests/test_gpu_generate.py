@@ -210,3 +210,30 @@ def test_full_specs_iterations_with_gpu_generation_match_the_oracle(beams, tau):
     for r in ("target", "draft", "prm"):
         assert step.prefixes[r].lens_dev.cpu().tolist() == [len(t) for t in traces]
     step.close()
+
+
+@pytest.mark.parametrize("B_,n,hq,hkv,lens", [(4, 9, 4, 2, (70, 200)),      # 36 rows per position: block-tiled GEMMs
+                                              (1, 40, 4, 1, (130, 131)),    # 160 stacked rows: two row tiles per kv head
+                                              (2, 16, 2, 2, (1, 20)),       # prefixes shorter than one key tile, down to 1
+                                              (1, 1, 2, 1, (64, 65))])      # a single candidate
+def test_generation_equals_scoring_at_other_row_counts(B_, n, hq, hkv, lens):
+    """The at-any-size property (generation log-likelihoods = block-parallel scoring of the same tokens) on shapes
+    that take the other code paths of the generation pass."""
+    from paper_2506_15733_amd import synthetic
+    d = hq * 64
+    t = ModelDesc("target", 2, d, hq, hkv, 64, 256, 777, "bf16", "lm")
+    dr = ModelDesc("draft", 1, d, hq, hkv, 64, 128, 777, "bf16", "lm")
+    p = ModelDesc("prm", 1, d, hq, hkv, 64, 128, 777, "bf16", "prm")
+    wl = Workload("gen_rows", t, dr, p, B=B_, n=n, L=7, prefix_len=0, lens_range=lens, betas=(1.0,),
+                  token_dist="uniform", page_tokens=16, seed=31, u_seed=32)
+    step = synthetic.ScoringStep(wl)
+    step.prefill()
+    u = W.rng.uniform_f64(wl.u_seed, "gen/u5", wl.B * wl.n * wl.L).reshape(wl.B, wl.n, wl.L)
+    cand, logp, tok = gpu_generate(step, "target", u)
+    assert cand.min() >= 0 and cand.max() < 777
+    step.cand = torch.from_numpy(cand).to(step.device)
+    step.score("target")
+    torch.cuda.synchronize()
+    assert np.abs(step.tok["target"].cpu().numpy() - tok).max() < 2e-2
+    assert np.abs(step.out["target"].cpu().numpy() - logp).max() < 2e-2 * np.sqrt(wl.L)
+    step.close()

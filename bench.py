@@ -217,8 +217,8 @@ def main():
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--rows", type=int, default=0, help="with --kernel: activation rows (default: the workload's B*n*L)")
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c4_7b")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--serial", action="store_true", help="one stream for the three passes instead of one each")

@@ -212,11 +212,13 @@ def test_full_specs_iterations_with_gpu_generation_match_the_oracle(beams, tau):
     step.close()
 
 
-@pytest.mark.parametrize("B_,n,hq,hkv,lens", [(4, 9, 4, 2, (70, 200)),      # 36 rows per position: block-tiled GEMMs
-                                              (1, 40, 4, 1, (130, 131)),    # 160 stacked rows: two row tiles per kv head
-                                              (2, 16, 2, 2, (1, 20)),       # prefixes shorter than one key tile, down to 1
-                                              (1, 1, 2, 1, (64, 65))])      # a single candidate
-def test_generation_equals_scoring_at_other_row_counts(B_, n, hq, hkv, lens):
+@pytest.mark.parametrize("B_,n,hq,hkv,lens,L", [
+    (4, 9, 4, 2, (70, 200), 7),       # 36 rows per position: block-tiled GEMMs
+    (1, 40, 4, 1, (130, 131), 7),     # 160 stacked rows: two row tiles per kv head
+    (2, 16, 2, 2, (1, 20), 7),        # prefixes shorter than one key tile, down to 1
+    (1, 1, 2, 1, (64, 65), 7),        # a single candidate
+    (1, 3, 2, 1, (30, 31), 131)])     # blocks longer than 128 tokens: the general merge kernel
+def test_generation_equals_scoring_at_other_row_counts(B_, n, hq, hkv, lens, L):
     """The at-any-size property (generation log-likelihoods = block-parallel scoring of the same tokens) on shapes
     that take the other code paths of the generation pass."""
     from paper_2506_15733_amd import synthetic
@@ -224,7 +226,7 @@ def test_generation_equals_scoring_at_other_row_counts(B_, n, hq, hkv, lens):
     t = ModelDesc("target", 2, d, hq, hkv, 64, 256, 777, "bf16", "lm")
     dr = ModelDesc("draft", 1, d, hq, hkv, 64, 128, 777, "bf16", "lm")
     p = ModelDesc("prm", 1, d, hq, hkv, 64, 128, 777, "bf16", "prm")
-    wl = Workload("gen_rows", t, dr, p, B=B_, n=n, L=7, prefix_len=0, lens_range=lens, betas=(1.0,),
+    wl = Workload("gen_rows", t, dr, p, B=B_, n=n, L=L, prefix_len=0, lens_range=lens, betas=(1.0,),
                   token_dist="uniform", page_tokens=16, seed=31, u_seed=32)
     step = synthetic.ScoringStep(wl)
     step.prefill()

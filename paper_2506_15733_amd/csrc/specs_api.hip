@@ -316,9 +316,11 @@ int gemm_residual_split<bf16_t>(const bf16_t* A, const bf16_t* W, float* x, floa
     int sp = skinny_gemm_split(N, K, max_split);
     if (launch_gemm_skinny(MFMA_STORE, A, W, M, N, K, part, nullptr, sp, s)) return sp;
   }
+  // Also with one slice the product goes to `part` and the normalisation kernel, which reads x anyway, adds it:
+  // the GEMM's epilogue then only writes, instead of waiting for a read of x before every store.
   int bm = 0, split = 1;
   if (K % 64 == 0 && max_split > 1) mfma_gemm_plan(M, N, K, max_split, &bm, &split);
-  if (split > 1 &&
+  if (max_split >= 1 &&
       launch_gemm_mfma(MFMA_STORE, A, W, M, N, K, part, nullptr, nullptr, nullptr, nullptr, nullptr, split, bm, s))
     return split;
   gemm<bf16_t>(A, W, x, M, N, K, EPI_RESIDUAL_ADD, s);

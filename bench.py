@@ -28,8 +28,13 @@ def role_flops(d, M, P_total_rows_ctx, n, L, B):
     per_layer = 2.0 * M * d.d_model * (qd + 2 * kvd) + 2.0 * M * qd * d.d_model + 2.0 * M * d.d_model * 2 * d.ffn \
         + 2.0 * M * d.ffn * d.d_model
     attn = 4.0 * d.n_q_heads * d.head_dim * (P_total_rows_ctx + B * n * L * (L + 1) / 2.0)
-    head = 2.0 * M * d.d_model * d.vocab if d.head == "lm" else 2.0 * B * n * d.d_model
-    return d.n_layers * (per_layer + attn) + head
+    if d.head == "lm":
+        return d.n_layers * (per_layer + attn) + 2.0 * M * d.d_model * d.vocab
+    # PRM: the reward reads the last token of every block only, so the last layer needs its keys/values for all M
+    # rows but its attention output, O projection and feed-forward for B*n rows
+    C = B * n
+    last = 2.0 * M * d.d_model * (qd + 2 * kvd) + (per_layer - 2.0 * M * d.d_model * (qd + 2 * kvd)) * C / M + attn / L
+    return (d.n_layers - 1) * (per_layer + attn) + last + 2.0 * C * d.d_model
 
 
 def cpu_baseline(wl, budget_layers=2, n_sub=2):

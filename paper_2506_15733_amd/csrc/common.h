@@ -74,7 +74,10 @@ void launch_prm_head(const float* x, const float* gain, const T* w, float* out, 
 void launch_copy_rows(const float* x, float* h_last, const BatchGeom& g, int d, const int32_t* chosen, hipStream_t s);
 // generation: xs[b*n + i] = h_last[b0 + b] (every candidate starts from the prefix's last hidden state)
 void launch_broadcast_hlast(const float* h_last, float* xs, const BatchGeom& g, int d, hipStream_t s);
-// generation: x[(c*L + L-1)] = xs[c] for every candidate c (the state at the last block token, where scoring leaves it)
+// dst[c][0..width) = src[(c*L + L-1)][0..width): the last row of every block
+template <typename T>
+void launch_gather_last_rows(const T* src, T* dst, int C, int L, int width, hipStream_t s);
+// x[(c*L + L-1)] = xs[c] for every candidate c (the state at the last block token, where scoring leaves it)
 void launch_scatter_last_rows(const float* xs, float* x, int C, int L, int d, hipStream_t s);
 // block_out[c] = sum_t tok_logp[c][t] in index order, accumulated in double
 void launch_block_sum(const float* tok_logp, float* block_out, int L, int C, hipStream_t s);

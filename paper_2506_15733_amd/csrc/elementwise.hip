@@ -384,6 +384,18 @@ void launch_broadcast_hlast(const float* h_last, float* xs, const BatchGeom& g, 
   broadcast_hlast_kernel<<<g.B * g.n, 256, 0, s>>>(h_last, xs, g.n, g.b0, d);
 }
 
+template <typename T>
+__global__ void gather_last_rows_kernel(const T* __restrict__ src, T* __restrict__ dst, int L, int width) {
+  size_t c = blockIdx.x;
+  for (int j = threadIdx.x; j < width; j += blockDim.x) dst[c * width + j] = src[(c * L + (L - 1)) * width + j];
+}
+template <typename T>
+void launch_gather_last_rows(const T* src, T* dst, int C, int L, int width, hipStream_t s) {
+  gather_last_rows_kernel<T><<<C, 256, 0, s>>>(src, dst, L, width);
+}
+template void launch_gather_last_rows<float>(const float*, float*, int, int, int, hipStream_t);
+template void launch_gather_last_rows<bf16_t>(const bf16_t*, bf16_t*, int, int, int, hipStream_t);
+
 __global__ void scatter_last_rows_kernel(const float* __restrict__ xs, float* __restrict__ x, int L, int d) {
   size_t c = blockIdx.x;
   for (int j = threadIdx.x; j < d; j += blockDim.x) x[(c * L + (L - 1)) * d + j] = xs[c * d + j];

@@ -53,7 +53,7 @@ struct Workspace {
   float* zt;         // [R]
   float* tokl;       // [R] per-token log-probs when the caller passes no buffer
   int32_t* chosen;   // [B]
-  float* xs;         // [C, d] residual stream of the one position a generation step processes (LM heads)
+  float* xs;         // [C, d] residual stream of one position per block (generation steps; the PRM's last layer)
   float* logits;     // [C, V] next-token logits of a generation step (LM heads)
   char* sample;      // per-chunk softmax statistics of the sampling kernels (LM heads)
   size_t total;
@@ -87,7 +87,7 @@ static Workspace carve(char* base, const specs_model_desc& d, int64_t R, int64_t
   w.tokl = (float*)take(R * 4);
   w.chosen = (int32_t*)take((size_t)(C > 0 ? C : 1) * 4);
   bool lm = d.head == SPECS_HEAD_LM;
-  w.xs = (float*)take(lm ? (size_t)C * d.d_model * 4 : 0);
+  w.xs = (float*)take((size_t)C * d.d_model * 4);
   w.logits = (float*)take(lm ? (size_t)C * d.vocab * 4 : 0);
   w.sample = take(lm ? sample_scratch_bytes((int)C) : 0);
   w.total = off;
@@ -384,10 +384,13 @@ static void attention(const T* q, const T* kb, const T* vbT, const T* pK, const 
 // positions of its own block. Row m embeds tokens[m * tok_stride]. Leaves the final residual stream in x and the
 // per-layer block keys/values in ws.kblk / ws.vblk (laid out for blocks of g.Lk tokens; a launch with g.L = 1 and
 // g.t0 = t adds position t of every block). commit_pages: also write them into the prefix pages (prefill).
+// last_token_only (whole-block launches): the caller reads x only at the last token of every block (the PRM head),
+// so after the last layer's keys and values exist for all rows, its attention output, O projection and
+// feed-forward run for that one row per block; the other rows of x are left as the last layer found them.
 template <typename T>
 static void run_trunk(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const Workspace& ws,
                       const BatchGeom& g, float* x, const int32_t* tokens, int tok_stride, int max_ctx,
-                      bool commit_pages, int64_t R, int64_t C, hipStream_t s) {
+                      bool commit_pages, int64_t R, int64_t C, hipStream_t s, bool last_token_only = false) {
   const specs_model_desc& d = m->desc;
   ModelDims md = dims_of(d);
   const int Lp = round16(g.Lk);
@@ -411,6 +414,33 @@ static void run_trunk(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
              qkv_parts = gemm_store_split<T>((const T*)ws.a, (const T*)L.wqkv, ws.qkv, (int)(R / g.M < 8 ? R / g.M : 8),
                                              g.M, qd + 2 * kvd, md.d, s));
     PROFILED(ctx, SPECS_K_OTHER, s, launch_rope_split<T>(ws.qkv, qkv_parts, ws.cs, (T*)ws.q, kb, vb, g, Lp, md, s));
+    if (last_token_only && l == d.n_layers - 1 && g.L > 1 && g.t0 == 0 && !commit_pages) {
+      BatchGeom gl = g;                                  // one row per block: its last position
+      gl.L = 1; gl.M = (int)C; gl.t0 = g.L - 1; gl.Lk = g.L;
+      T* q1 = (T*)ws.a;                                  // the projection has consumed ws.a
+      PROFILED(ctx, SPECS_K_OTHER, s,
+               launch_gather_last_rows<T>((const T*)ws.q, q1, (int)C, g.L, qd, s);
+               launch_gather_last_rows<float>(x, ws.xs, (int)C, g.L, md.d, s));
+      PROFILED(ctx, SPECS_K_ATTENTION, s,
+               attention<T>(q1, kb, vb, pK, pV, (T*)ws.attn, gl, md, Lp, max_ctx, ws.gu, (size_t)R * 2 * md.F, s));
+      int pl = 0;
+      PROFILED(ctx, SPECS_K_OPROJ, s,
+               pl = gemm_residual_split<T>((const T*)ws.attn, (const T*)L.wo, ws.xs, ws.gu, max_split, gl.M, md.d, qd, s));
+      if (pl)
+        PROFILED(ctx, SPECS_K_OTHER, s,
+                 launch_add_partials_rmsnorm<T>(ws.xs, ws.gu, pl, 0, L.g_ffn, (T*)ws.a, gl.M, md.d, md.eps, s));
+      else
+        PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(ws.xs, L.g_ffn, (T*)ws.a, gl.M, md.d, md.eps, s));
+      PROFILED(ctx, SPECS_K_GATE_UP, s,
+               gate_up<T>((const T*)ws.a, (const T*)L.wgu, ws.gu, (T*)ws.act, gl.M, md.F, md.d, s));
+      PROFILED(ctx, SPECS_K_DOWN, s,
+               pl = gemm_residual_split<T>((const T*)ws.act, (const T*)L.wd, ws.xs, ws.gu, max_split, gl.M, md.d, md.F, s));
+      if (pl)
+        PROFILED(ctx, SPECS_K_OTHER, s,
+                 launch_add_partials_rmsnorm<T>(ws.xs, ws.gu, pl, 0, nullptr, (T*)ws.a, gl.M, md.d, md.eps, s));
+      PROFILED(ctx, SPECS_K_OTHER, s, launch_scatter_last_rows(ws.xs, x, (int)C, g.L, md.d, s));
+      break;
+    }
     PROFILED(ctx, SPECS_K_ATTENTION, s,
              attention<T>((const T*)ws.q, kb, vb, pK, pV, (T*)ws.attn, g, md, Lp, max_ctx, ws.gu,
                           (size_t)R * 2 * md.F, s));
@@ -450,7 +480,7 @@ static int score_impl(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
   int max_ctx = 0;
   for (int b = 0; b < p->B; ++b) max_ctx = p->lens[b] > max_ctx ? p->lens[b] : max_ctx;
   hipStream_t s = ctx->stream;
-  run_trunk<T>(ctx, m, p, ws, g, ws.x, cand, 1, max_ctx, false, R, C, s);
+  run_trunk<T>(ctx, m, p, ws, g, ws.x, cand, 1, max_ctx, false, R, C, s, d.head == SPECS_HEAD_PRM);
   if (d.head == SPECS_HEAD_LM) {
     int tiles = 0;
     PROFILED(ctx, SPECS_K_OTHER, s,

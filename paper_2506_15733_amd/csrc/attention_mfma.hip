@@ -42,7 +42,7 @@ struct AttnArgs {
   // single-position launches (generation): the prefix keys are cut into n_splits runs of tiles and every
   // workgroup leaves an un-normalised partial result for a second kernel to merge
   int n_splits;
-  float* part_o;        // [(b*Hkv + kvh)][q_tile][split][128][HD]
+  float* part_o;        // [(b*Hkv + kvh) (, candidate)][q_tile][split][128][HD]
   float* part_m;        // [..][128] running maximum (log2 domain), -inf if the run was empty
   float* part_l;        // [..][128] sum of weights relative to that maximum
 };
@@ -52,12 +52,15 @@ __device__ __forceinline__ int k_swizzle(int row, int chunk) {
   return HD == 128 ? (chunk ^ (row & 15)) : (chunk ^ ((row >> 1) & 7));
 }
 
-// DEC = false: whole blocks, as described above. DEC = true: one position per candidate; the stacked rows of a
+// MODE 0: whole blocks, as described above. MODE 1: one position per candidate; the stacked rows of a
 // (beam, kv head) are its n candidates x g query heads (row r = i*g + j), the workgroup covers only the prefix
 // tiles of its split and writes (O un-normalised, m, l) instead of the output; the candidate's own block keys
-// are added by the merge kernel.
-template <int HD, int QT, bool DEC>
+// are added by the merge kernel. MODE 2: whole blocks, but the tile list (prefix tiles, then block tiles) is cut
+// into n_splits runs handled by different workgroups, for launches that would otherwise leave most CUs idle; a
+// merge kernel combines the partial results.
+template <int HD, int QT, int MODE>
 __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(AttnArgs a) {
+  constexpr bool DEC = MODE == 1, SPLIT = MODE != 0;
   constexpr int KROW = HD * 2;              // bytes per key row
   constexpr int KCH = HD / 8;               // 16-byte chunks per key row
   constexpr int K_BYTES = 64 * KROW;        // 64 keys
@@ -75,7 +78,7 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
   const int g = a.Hq / a.Hkv;
   int rem = logical;
   int split = 0;
-  if (DEC) { split = rem % a.n_splits; rem /= a.n_splits; }
+  if (SPLIT) { split = rem % a.n_splits; rem /= a.n_splits; }
   const int qt_idx = rem % a.q_tiles; rem /= a.q_tiles;
   int cand = 0;
   if (!DEC) { cand = rem % G.n; rem /= G.n; }
@@ -125,8 +128,9 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
   t_hi = t_hi < L - 1 ? t_hi : L - 1;
   const int n_btiles = DEC ? 0 : ((r_wg0 < rows_total) ? (t_hi >> 6) + 1 : 0);
   // tiles [tile_lo, tile_lo + n_tiles) of the list (prefix tiles, then block tiles)
-  const int tile_lo = DEC ? (int)((long)split * n_ptiles / a.n_splits) : 0;
-  const int n_tiles = DEC ? (int)((long)(split + 1) * n_ptiles / a.n_splits) - tile_lo : n_ptiles + n_btiles;
+  const int n_list = n_ptiles + n_btiles;
+  const int tile_lo = SPLIT ? (int)((long)split * n_list / a.n_splits) : 0;
+  const int n_tiles = SPLIT ? (int)((long)(split + 1) * n_list / a.n_splits) - tile_lo : n_list;
 
   // one wavefront stages one 16-key group (a page, or 16 block tokens) of the tile: K rows and V^T
   auto stage_tile = [&](int tile, char* buf) {
@@ -270,9 +274,9 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
   for (int u = 0; u < QT; ++u) {
     int r = r_wg0 + (wave * QT + u) * 32 + lq;
     float l = l_run[u] + __shfl_xor(l_run[u], 32, 64);
-    if (DEC) {
-      const size_t prow = ((((size_t)b * a.Hkv + kvh) * a.q_tiles + qt_idx) * a.n_splits + split) * 128 +
-                          (wave * QT + u) * 32 + lq;
+    if (SPLIT) {
+      const size_t group = DEC ? (size_t)b * a.Hkv + kvh : ((size_t)b * a.Hkv + kvh) * G.n + cand;
+      const size_t prow = ((group * a.q_tiles + qt_idx) * a.n_splits + split) * BQ + (wave * QT + u) * 32 + lq;
       if (lh == 0) { a.part_m[prow] = m_run[u]; a.part_l[prow] = l; }
       float* dst = a.part_o + prow * HD;
 #pragma unroll
@@ -298,22 +302,56 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
   }
 }
 
-template <int HD, int QT, bool DEC = false>
+template <int HD, int QT, int MODE = 0>
 static void launch_attn_variant(const AttnArgs& a, hipStream_t s) {
   constexpr int smem = 2 * (64 * HD * 2 + 4 * HD * 32);
   static bool configured = false;
   if (!configured) {
-    (void)hipFuncSetAttribute((const void*)attention_mfma_kernel<HD, QT, DEC>,
+    (void)hipFuncSetAttribute((const void*)attention_mfma_kernel<HD, QT, MODE>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     configured = true;
   }
-  attention_mfma_kernel<HD, QT, DEC><<<dim3(a.wg_per_xcd * 8), 256, smem, s>>>(a);
+  attention_mfma_kernel<HD, QT, MODE><<<dim3(a.wg_per_xcd * 8), 256, smem, s>>>(a);
+}
+
+// Merge of the partial results of a MODE 2 launch: one wavefront per (row, query head).
+template <int HD>
+__global__ void __launch_bounds__(64) attention_split_merge_kernel(const float* __restrict__ part_o,
+                                                                   const float* __restrict__ part_m,
+                                                                   const float* __restrict__ part_l,
+                                                                   bf16_t* __restrict__ out, int n, int L, int Hq, int Hkv,
+                                                                   int q_tiles, int n_splits) {
+  const size_t m = blockIdx.x;
+  const int h = blockIdx.y, lane = threadIdx.x;
+  const int g = Hq / Hkv, kvh = h / g, j = h - kvh * g;
+  const size_t cand_idx = m / L;                           // b*n + i
+  const int t = (int)(m - cand_idx * L);
+  const int r = t * g + j, qt = r >> 7, rin = r & 127;
+  const size_t b = cand_idx / n, i = cand_idx - b * n;
+  const size_t group = (b * Hkv + kvh) * n + i;
+  const size_t prow0 = (group * q_tiles + qt) * n_splits * 128 + rin;      // + split*128
+  float mx = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, part_m[prow0 + (size_t)s * 128]);
+  float l = 0.f, acc[HD / 64];
+#pragma unroll
+  for (int u = 0; u < HD / 64; ++u) acc[u] = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const size_t pr = prow0 + (size_t)s * 128;
+    const float w = __builtin_amdgcn_exp2f(part_m[pr] - mx);   // 0 for a run that saw no visible key
+    l = fmaf(w, part_l[pr], l);
+#pragma unroll
+    for (int u = 0; u < HD / 64; ++u) acc[u] = fmaf(w, part_o[pr * HD + lane + 64 * u], acc[u]);
+  }
+  const float inv = 1.0f / l;
+#pragma unroll
+  for (int u = 0; u < HD / 64; ++u) out[(m * Hq + h) * HD + lane + 64 * u] = (bf16_t)(acc[u] * inv);
 }
 
 // Returns false if the shape is not one this kernel takes (head_dim 64/128, 16-token pages).
+// part: scratch of part_floats floats for launches whose key tiles are split over several workgroups (may be null).
 bool launch_attention_mfma(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT, const bf16_t* poolK,
                            const bf16_t* poolV, bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp,
-                           hipStream_t s) {
+                           int max_ctx, float* part, size_t part_floats, hipStream_t s) {
   if ((md.hd != 64 && md.hd != 128) || g.page_tokens != 16 || Lp % 16 != 0) return false;
   AttnArgs a;
   a.q = q; a.kb = kb; a.vbT = vbT; a.poolK = poolK; a.poolV = poolV; a.out = out; a.g = g;
@@ -326,6 +364,34 @@ bool launch_attention_mfma(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT,
   bool big = t2 * 256 < t1 * 128;
   a.q_tiles = big ? t2 : t1;
   a.total_wg = g.B * md.Hkv * g.n * a.q_tiles;
+  // Few workgroups and a long key list: cut the list so that about two workgroups per CU exist, at least four
+  // tiles per run, at most eight runs.
+  int list_tiles = (max_ctx + 63) / 64 + (g.L + 63) / 64;
+  int splits = 1;
+  if (!big && part && a.total_wg < 384 && list_tiles >= 16) {   // short lists: a second kernel costs more than it saves
+    splits = (512 + a.total_wg - 1) / a.total_wg;
+    splits = splits > 8 ? 8 : splits;
+    splits = splits > list_tiles / 4 ? list_tiles / 4 : splits;
+    size_t per_split = (size_t)a.total_wg * 128 * (md.hd + 2);
+    if (splits > 1 && (size_t)splits * per_split > part_floats) splits = (int)(part_floats / per_split);
+    if (splits < 1) splits = 1;
+  }
+  if (splits > 1) {
+    size_t rows_all = (size_t)a.total_wg * splits * 128;
+    a.n_splits = splits;
+    a.part_o = part; a.part_m = part + rows_all * md.hd; a.part_l = a.part_m + rows_all;
+    a.total_wg *= splits;
+    a.wg_per_xcd = (a.total_wg + 7) / 8;
+    if (md.hd == 128) launch_attn_variant<128, 1, 2>(a, s); else launch_attn_variant<64, 1, 2>(a, s);
+    dim3 grid(g.M, md.Hq);
+    if (md.hd == 128)
+      attention_split_merge_kernel<128><<<grid, 64, 0, s>>>(a.part_o, a.part_m, a.part_l, out, g.n, g.L, md.Hq, md.Hkv,
+                                                           a.q_tiles, splits);
+    else
+      attention_split_merge_kernel<64><<<grid, 64, 0, s>>>(a.part_o, a.part_m, a.part_l, out, g.n, g.L, md.Hq, md.Hkv,
+                                                          a.q_tiles, splits);
+    return true;
+  }
   a.wg_per_xcd = (a.total_wg + 7) / 8;
   if (md.hd == 128) { if (big) launch_attn_variant<128, 2>(a, s); else launch_attn_variant<128, 1>(a, s); }
   else { if (big) launch_attn_variant<64, 2>(a, s); else launch_attn_variant<64, 1>(a, s); }
@@ -361,8 +427,8 @@ bool launch_attention_mfma_decode_prefix(const bf16_t* q, const bf16_t* poolK, c
   a.part_l = a.part_m + rows_all;
   a.total_wg = base * splits;
   a.wg_per_xcd = (a.total_wg + 7) / 8;
-  if (md.hd == 128) launch_attn_variant<128, 1, true>(a, s);
-  else launch_attn_variant<64, 1, true>(a, s);
+  if (md.hd == 128) launch_attn_variant<128, 1, 1>(a, s);
+  else launch_attn_variant<64, 1, 1>(a, s);
   *q_tiles_out = a.q_tiles;
   *n_splits_out = splits;
   return true;

@@ -96,9 +96,10 @@ void launch_gemm_simple(const T* A, const T* W, float* C, int M, int N, int K, G
 template <typename T>
 void launch_attention_simple(const T* q, const T* kb, const T* vbT, const T* poolK, const T* poolV, T* out,
                              const BatchGeom& g, const ModelDims& md, int Lp, int max_ctx, hipStream_t s);
+// part / part_floats: float scratch for launches that split the key tiles over workgroups (null: never split)
 bool launch_attention_mfma(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT, const bf16_t* poolK,
                            const bf16_t* poolV, bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp,
-                           hipStream_t s);
+                           int max_ctx, float* part, size_t part_floats, hipStream_t s);
 
 // One in-block position per candidate (g.L == 1, position g.t0): prefix keys by the MFMA kernel in split mode,
 // merged with the candidate's own block keys. part: scratch of part_floats floats. False if the shape is not taken.

@@ -741,7 +741,7 @@ void attention<bf16_t>(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT, con
                        bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp, int max_ctx, float* scratch,
                        size_t scratch_floats, hipStream_t s) {
   bool whole_blocks = g.t0 == 0 && g.Lk == g.L;
-  bool done = whole_blocks ? launch_attention_mfma(q, kb, vbT, pK, pV, out, g, md, Lp, s)
+  bool done = whole_blocks ? launch_attention_mfma(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, scratch, scratch_floats, s)
                            : (g.L == 1 && scratch &&
                               launch_attention_decode(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, scratch,
                                                       scratch_floats, s));

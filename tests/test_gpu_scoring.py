@@ -153,9 +153,20 @@ def mfma_ragged_workload():
                     token_dist="zipf", page_tokens=16, seed=14, u_seed=12)
 
 
-@pytest.mark.parametrize("kind", ["f32", "bf16", "bf16_mfma"])
+def long_prefix_workload():
+    """bf16 MFMA shapes with prefixes of 17 to 24 key tiles and few (beam, kv head, candidate) groups: the launch
+    that cuts the key-tile list of a block over several workgroups and merges their partial results."""
+    t = ModelDesc("target", 2, 256, 2, 1, 128, 320, 500, "bf16", "lm")
+    d = ModelDesc("draft", 1, 128, 2, 2, 64, 192, 500, "bf16", "lm")
+    p = ModelDesc("prm", 1, 256, 2, 1, 128, 320, 500, "bf16", "prm")
+    return Workload("long_prefix", t, d, p, B=2, n=2, L=70, prefix_len=0, lens_range=(1050, 1500), betas=(1.0,),
+                    token_dist="zipf", page_tokens=16, seed=17, u_seed=18)
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16", "bf16_mfma", "bf16_long_prefix"])
 def test_ragged_shapes_several_beams_shuffled_pages(kind):
-    wl = mfma_ragged_workload() if kind == "bf16_mfma" else ragged_workload(kind)
+    wl = (mfma_ragged_workload() if kind == "bf16_mfma" else long_prefix_workload() if kind == "bf16_long_prefix"
+          else ragged_workload(kind))
     dtype = "f32" if kind == "f32" else "bf16"
     assert len(set(wl.prefix_lens().tolist())) == wl.B
     step, res = run_step(wl)

@@ -239,3 +239,33 @@ def test_generation_equals_scoring_at_other_row_counts(B_, n, hq, hkv, lens, L):
     assert np.abs(step.tok["target"].cpu().numpy() - tok).max() < 2e-2
     assert np.abs(step.out["target"].cpu().numpy() - logp).max() < 2e-2 * np.sqrt(wl.L)
     step.close()
+
+
+def test_generation_equals_scoring_at_config_4_size():
+    """Full benchmark size (1.5B draft of config 4: 16 candidates x 128 positions on a 4096-token prefix, the launch
+    configuration `bench.py --generate draft` times): the block log-likelihoods that come out of generation equal
+    what the block-parallel scoring pass assigns to the generated tokens, within the bf16 sensitivity the oracle
+    measured for this model (tests/golden/oracle_c4_7b.json, noise_draft), and every id is in range."""
+    import json, os
+    from paper_2506_15733_amd import synthetic
+    wl = W.get_config("c4_7b")
+    path = os.path.join(os.path.dirname(__file__), "golden", "oracle_c4_7b.json")
+    noise = json.load(open(path)).get("noise_draft") if os.path.exists(path) else None
+    if noise is None:
+        pytest.skip("oracle sensitivity for the 1.5B model not stored")
+    step = synthetic.ScoringStep(wl)
+    step.prefill()
+    u = W.rng.uniform_f64(wl.u_seed, "gen/c4", wl.B * wl.n * wl.L).reshape(wl.B, wl.n, wl.L)
+    cand, logp, tok = gpu_generate(step, "draft", u, vocab_limit=wl.draft.vocab)
+    assert cand.min() >= 0 and cand.max() < wl.draft.vocab and len(np.unique(cand)) > 500
+    step.cand = torch.from_numpy(cand).to(step.device)
+    step.score("draft")
+    torch.cuda.synchronize()
+    dt = np.abs(step.tok["draft"].cpu().numpy() - tok)
+    db = np.abs(step.out["draft"].cpu().numpy() - logp)
+    print("generation vs scoring at config 4:", dict(tok_max=float(dt.max()), tok_rms=float(np.sqrt((dt ** 2).mean())),
+                                                     block_max=float(db.max())), "sensitivity", noise)
+    assert dt.max() < max(2e-2, 2 * noise["tok_max"])
+    assert np.sqrt((dt ** 2).mean()) < max(5e-3, 1.5 * noise["tok_rms"])
+    assert db.max() < max(2e-2, 2 * noise["block_max"])
+    step.close()

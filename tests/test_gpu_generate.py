@@ -269,3 +269,27 @@ def test_generation_equals_scoring_at_config_4_size():
     assert np.sqrt((dt ** 2).mean()) < max(5e-3, 1.5 * noise["tok_rms"])
     assert db.max() < max(2e-2, 2 * noise["block_max"])
     step.close()
+
+
+def test_generation_loop_on_mfma_shapes_is_valid_and_reproducible():
+    """bf16 models on the MFMA kernels: H iterations of Alg. 1 with GPU generation run twice from scratch give
+    identical tokens, choices and switching decisions; ids are in range, caches advance by L per iteration."""
+    from paper_2506_15733_amd import synthetic, binding as B
+    wl = mfma_workload()
+    H = 3
+    runs = []
+    for _ in range(2):
+        step = synthetic.ScoringStep(wl, extra_tokens=H * wl.L)
+        step.prefill()
+        tokens, chosen, gen = synthetic.run_specs_generation_loop(step, H, 0.5)
+        assert all(v == 0 for v in step.status().values())
+        for r in ("target", "draft", "prm"):
+            assert step.prefixes[r].lens_dev.cpu().tolist() == (wl.prefix_lens() + H * wl.L).tolist()
+        runs.append((tokens, chosen, gen))
+        step.close()
+    for a, b in zip(*runs):
+        assert np.array_equal(a, b)
+    tokens, chosen, gen = runs[0]
+    assert tokens.shape == (H, wl.B, wl.n, wl.L) and tokens.min() >= 0 and tokens.max() < 1000
+    assert chosen.min() >= 0 and chosen.max() < wl.n
+    assert not gen[0].any()                                   # every beam starts with the target as its generator

@@ -66,6 +66,7 @@ def load_library():
     lib.specs_prefix_destroy.argtypes = [vp]
     lib.specs_prefill.argtypes = [vp, vp, vp, vp]
     lib.specs_score_blocks.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp]
+    lib.specs_generate_blocks.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.specs_commit_block.argtypes = [vp, vp, vp, C.POINTER(i32)]
     lib.specs_subsample.argtypes = [vp, vp, vp, vp, vp, i32, i32, C.POINTER(C.c_float), i32, vp, vp, vp]
     lib.specs_ctx_profile.argtypes = [vp, C.c_int]

@@ -293,3 +293,30 @@ def test_generation_loop_on_mfma_shapes_is_valid_and_reproducible():
     assert tokens.shape == (H, wl.B, wl.n, wl.L) and tokens.min() >= 0 and tokens.max() < 1000
     assert chosen.min() >= 0 and chosen.max() < wl.n
     assert not gen[0].any()                                   # every beam starts with the target as its generator
+
+
+def test_generation_rejects_bad_arguments():
+    from paper_2506_15733_amd import synthetic, binding as B
+    wl = small_workload("f32", B=1, n=2, L=3)
+    step = synthetic.ScoringStep(wl)
+    step.prefill()
+    dm, pf = step.models["draft"], step.prefixes["draft"]
+    u = torch.zeros((1, 2, 3), dtype=torch.float64, device=step.device)
+    c = torch.zeros((1, 2, 3), dtype=torch.int32, device=step.device)
+    lp = torch.zeros((1, 2), dtype=torch.float32, device=step.device)
+    lib = B.load_library()
+    import ctypes as C
+    p = lambda t: C.c_void_p(t.data_ptr())
+    assert lib.specs_generate_blocks(dm.ctx, dm.model, pf.handle, 0, 3, 0, p(u), p(c), p(lp), None) == 1      # n = 0
+    assert lib.specs_generate_blocks(dm.ctx, dm.model, pf.handle, 2, 3, 302, p(u), p(c), p(lp), None) == 1    # limit > V
+    assert lib.specs_generate_blocks(dm.ctx, dm.model, pf.handle, 2, 3, 0, None, p(c), p(lp), None) == 1      # no uniforms
+    other = step.prefixes["target"].handle                                                                   # wrong prefix
+    assert lib.specs_generate_blocks(dm.ctx, dm.model, other, 2, 3, 0, p(u), p(c), p(lp), None) == 1
+    big_u = torch.zeros((1, 64, 64), dtype=torch.float64, device=step.device)                                # beyond the workspace
+    big_c = torch.zeros((1, 64, 64), dtype=torch.int32, device=step.device)
+    big_lp = torch.zeros((1, 64), dtype=torch.float32, device=step.device)
+    assert lib.specs_generate_blocks(dm.ctx, dm.model, pf.handle, 64, 64, 0, p(big_u), p(big_c), p(big_lp), None) == 7
+    B.specs_generate_blocks(dm.ctx, dm.model, pf.handle, u, c, lp)                                           # still usable
+    torch.cuda.synchronize()
+    assert B.specs_ctx_status(dm.ctx) == 0 and c.max().item() < 301
+    step.close()

@@ -292,6 +292,14 @@ def main():
 
     lens = wl.prefix_lens()
     ctx_rows = float(sum(int(l) * wl.n * wl.L for l in lens))
+    # fraction of the bf16 MFMA peak of every contraction of the target pass, from the same live per-launch times
+    qd, kvd = d.n_q_heads * d.head_dim, d.n_kv_heads * d.head_dim
+    kflops = {"qkv": 2.0 * M * d.d_model * (qd + 2 * kvd), "oproj": 2.0 * M * qd * d.d_model,
+              "gate_up": 2.0 * M * d.d_model * 2 * d.ffn, "down": 2.0 * M * d.ffn * d.d_model,
+              "lmhead": 2.0 * M * d.d_model * d.vocab,
+              "attention": 4.0 * qd * (ctx_rows + wl.B * wl.n * wl.L * (wl.L + 1) / 2.0)}
+    kfrac = {k: (v / (kernel_us[k] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS if kernel_us.get(k) else None)
+             for k, v in kflops.items()}
     total_flops = sum(role_flops(m, M, ctx_rows, wl.n, wl.L, wl.B) for m in wl.models().values())
     line = {
         "metric": "candidate tokens scored/sec (n blocks x L) on 1 MI355X",
@@ -301,7 +309,7 @@ def main():
         "config": {"workload": wl.name, "B": wl.B, "n": wl.n, "L": wl.L, "prefix_tokens": int(lens.sum()),
                    "roles": "target+draft+prm+subsample", "streams": 1 if args.serial else 3},
         "step_tflops": total_flops / dt / 1e12, "step_frac_of_mfma_peak": total_flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-        "role_ms_alone": role_ms, "target_kernel_us_per_launch": kernel_us,
+        "role_ms_alone": role_ms, "target_kernel_us_per_launch": kernel_us, "target_kernel_frac_of_mfma_peak": kfrac,
         "roofline": {"kernel": "gemm_mfma_kernel<256, SWIGLU> (gate/up projection + SiLU*mul)", "bound": "mfma",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "ms_per_launch": k_ms,

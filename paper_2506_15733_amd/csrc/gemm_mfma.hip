@@ -15,6 +15,7 @@
 // output; vocabulary head: per-row (max, sum exp) over the tile's 256 columns plus the logit of
 // the row's target token, so that logits never reach memory.
 #include "common.h"
+#include <type_traits>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -103,7 +104,7 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   const int KT = (int)((long)(blockIdx.y + 1) * (a.K / 64) / a.ksplit) - kt0;
   // LDS ring of five slots; a slot holds one operand tile (A: BM x 64, W: 256 x 64). K-tile t uses slot 2t for
   // W and slot 2t+1 for A (mod 5), so besides the two slots being multiplied three are in flight: the weights,
-  // which stream from HBM, are requested two K-tiles ahead, the activations one and a half.
+  // which stream from HBM, are requested about two K-tiles ahead, the activations about one.
   constexpr int SLOT = 256 * 128;
   auto wslot = [&](int t) { return smem + ((2 * t) % 5) * SLOT; };
   auto aslot = [&](int t) { return smem + ((2 * t + 1) % 5) * SLOT; };
@@ -133,47 +134,65 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
 #pragma unroll
     for (int i = 0; i < LA; ++i) load_span_async<NW>(a.A, m0, a.M, a.K, (kt0 + src) * 64, aslot(t), i);
   };
-  // One k-step of the software pipeline: two MFMAs of the current group go first, then the LDS reads of the
-  // next group (and, after the barrier, the global loads that refill the two freed slots) are issued, then the
-  // rest of the MFMAs. Nothing in the group waits on those reads.
-#define PIPE_STEP_ORDER(NLOADS)                                        \
-  __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                   \
-  __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);             \
-  __builtin_amdgcn_sched_group_barrier(0x010, NLOADS, 0);              \
-  __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - 2, 0);         \
+  // The loads that refill the two slots a barrier frees, A(t+1) then W(t+2), are dealt into four shares: share 0
+  // goes out right behind that barrier, shares 1..3 with the first three MFMA groups of the next k-step. A burst of
+  // all of them at one point fills the vector-memory queue, and the MFMAs behind a queued load wait with it.
+  constexpr int NLD = LA + LB;
+  auto share_size = [](int sh) { int c = 0; for (int j = 0; j < NLD; ++j) c += (j * 4 / NLD == sh); return c; };
+  constexpr int S0 = share_size(0), S1 = share_size(1), S2 = share_size(2), S3 = share_size(3);
+  static_assert(LB == 4 && (S0 == 2) && S1 <= 2 && S2 <= 2 && S3 <= 2, "the waits below are written for these counts");
+  auto issue_share = [&](int ta, int tw, auto share) {
+    constexpr int SH = decltype(share)::value;
+    const int sa = ta < KT ? ta : KT - 1, sw = tw < KT ? tw : KT - 1;   // past the end: redundant loads into free slots
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+      if (j * 4 / NLD != SH) continue;
+      if (j < LA) load_span_async<NW>(a.A, m0, a.M, a.K, (kt0 + sa) * 64, aslot(ta), j);
+      else load_span_async<NW>(a.W, n0, a.N, a.K, (kt0 + sw) * 64, wslot(tw), j - LA);
+    }
+  };
+  // One MFMA group of the software pipeline: two MFMAs go first, then the LDS reads of the next group, then the rest
+  // of the MFMAs with the group's (at most two) global loads between them, three MFMAs apart. Nothing in the group
+  // waits on those reads or loads.
+#define SGB __builtin_amdgcn_sched_group_barrier
+#define PIPE_GROUP_ORDER(NLOADS)                                                                                   \
+  SGB(0x008, 2, 0);                                                                                                \
+  SGB(0x100, TM + TN, 0);                                                                                          \
+  if (NLOADS == 1) { SGB(0x008, 3, 0); SGB(0x010, 1, 0); SGB(0x008, TM * TN - 5, 0); }                             \
+  else if (NLOADS == 2) { SGB(0x008, 1, 0); SGB(0x010, 1, 0); SGB(0x008, 3, 0); SGB(0x010, 1, 0); SGB(0x008, TM * TN - 6, 0); } \
+  else SGB(0x008, TM * TN - 2, 0);                                                                                 \
   __builtin_amdgcn_sched_barrier(0)
 
-  issue_w(0); issue_a(0); issue_w(1); issue_a(1); issue_w(2);
-  // K-tile 0 has landed when only the three younger slots (W1, A1, W2) are still in flight
-  if (2 * LB + LA == 12) asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
-  else if (2 * LB + LA == 10) asm volatile("s_waitcnt vmcnt(10)\n\ts_barrier" ::: "memory");
-  else if (2 * LB + LA == 24) asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
-  else { static_assert(2 * LB + LA == 12 || 2 * LB + LA == 10 || 2 * LB + LA == 24 || 2 * LB + LA == 20, "");
-         asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory"); }
+  issue_w(0); issue_a(0); issue_w(1);
+  issue_share(1, 2, std::integral_constant<int, 0>{});
+  // K-tile 0 has landed when only W1 and the two loads of the first share are still in flight
+  asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");
   bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
   read_frags(0, 0, a0, b0);
   for (int kt = 0; kt < KT; ++kt) {
-    // The loop body is branch-free so that each k-step stays one scheduling region.
+    // The loop body is branch-free so that each MFMA group stays one scheduling region.
     read_frags(kt, 1, a1, b1);
+    issue_share(kt + 1, kt + 2, std::integral_constant<int, 1>{});
     mma(a0, b0);
-    PIPE_STEP_ORDER(0);
+    PIPE_GROUP_ORDER(S1);
     read_frags(kt, 2, a0, b0);
+    issue_share(kt + 1, kt + 2, std::integral_constant<int, 2>{});
     mma(a1, b1);
-    PIPE_STEP_ORDER(0);
+    PIPE_GROUP_ORDER(S2);
     read_frags(kt, 3, a1, b1);
+    issue_share(kt + 1, kt + 2, std::integral_constant<int, 3>{});
     mma(a0, b0);
-    PIPE_STEP_ORDER(0);
-    // Publish K-tile kt+1 (only W of K-tile kt+2 may still be in flight) and retire K-tile kt: own reads of it
-    // are complete, and after the barrier so are everybody's, so its two slots are refilled at once.
-    if (LB == 4) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    issue_a(kt + 2);
-    issue_w(kt + 3);
+    PIPE_GROUP_ORDER(S3);
+    // Publish K-tile kt+1 (loads complete in order, and the four youngest are W of K-tile kt+2) and retire K-tile
+    // kt: own reads of it are complete, and after the barrier so are everybody's, so its two slots can be refilled.
+    asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    issue_share(kt + 2, kt + 3, std::integral_constant<int, 0>{});
     read_frags(kt + 1 < KT ? kt + 1 : kt, 0, a0, b0);
     mma(a1, b1);
-    PIPE_STEP_ORDER(LA + LB);
+    PIPE_GROUP_ORDER(S0);
   }
-#undef PIPE_STEP_ORDER
+#undef PIPE_GROUP_ORDER
+#undef SGB
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // accumulator element r of lane: row 8*(r/4) + 4*lhalf + r%4, column lrow of the 32x32 tile

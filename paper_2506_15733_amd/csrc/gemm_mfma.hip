@@ -44,8 +44,8 @@ struct GemmArgs {
 // (8 rows of 128 bytes each) of an operand tile.
 template <int NW>
 __device__ __forceinline__ void load_span_async(const bf16_t* __restrict__ G, int row0, int rows_total, int K, int k0,
-                                                char* lds_tile, int p) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+                                                char* lds_tile, int p, int wave) {
+  const int lane = threadIdx.x & 63;
   int span = p * NW + wave;                  // 1 KiB of LDS = 8 rows, written by one wavefront
   int q = span * 64 + lane;
   int row = q >> 3, slot = q & 7;
@@ -74,6 +74,10 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   constexpr int BN = 256;
   constexpr int NW = 2 * NWN;                         // wavefronts: 2 along M x NWN along N
   constexpr int WM = BM / 2, TM = WM / 32, WN = BN / NWN, TN = WN / 32;
+  // The storing epilogues multiply W-fragment x A-fragment, i.e. the transposed 32x32 product: a lane then holds
+  // runs of four consecutive COLUMNS of one row of C and stores them as one 16-byte (8-byte bf16) piece; with the
+  // operands the other way round it holds single elements of four rows and needs four times the store instructions.
+  constexpr bool TRANS = EPI != ME_LMHEAD;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   // id -> (m_tile, n_tile): ids congruent mod 8 share an XCD. An XCD owns the N-tiles n = 8j + xcd; the 32
@@ -87,7 +91,7 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   if (n_tile >= a.n_tiles || m_tile >= a.m_tiles) return;
   const int m0 = m_tile * BM, n0 = n_tile * BN;
 
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wm = wave / NWN, wn = wave % NWN;
   const int lrow = lane & 31, lhalf = lane >> 5;
 
@@ -106,11 +110,12 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   // W and slot 2t+1 for A (mod 5), so besides the two slots being multiplied three are in flight: the weights,
   // which stream from HBM, are requested about two K-tiles ahead, the activations about one.
   constexpr int SLOT = 256 * 128;
-  auto wslot = [&](int t) { return smem + ((2 * t) % 5) * SLOT; };
-  auto aslot = [&](int t) { return smem + ((2 * t + 1) % 5) * SLOT; };
-  auto read_frags = [&](int t, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
-    const char* As = aslot(t);
-    const char* Bs = wslot(t);
+  // phase = K-tile index mod 5; the k-loop is unrolled five times so that every slot address is a constant
+  auto wslot = [&](int ph) { return smem + ((2 * ph) % 5) * SLOT; };
+  auto aslot = [&](int ph) { return smem + ((2 * ph + 1) % 5) * SLOT; };
+  auto read_frags = [&](int ph, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
+    const char* As = aslot(ph);
+    const char* Bs = wslot(ph);
 #pragma unroll
     for (int i = 0; i < TM; ++i) af[i] = lds_frag(As, wm * WM + i * 32 + lrow, ks * 2 + lhalf);
 #pragma unroll
@@ -121,39 +126,35 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        acc[i][j] = TRANS ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0)
+                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
   };
   constexpr int LA = BM / (8 * NW), LB = BN / (8 * NW);   // direct-to-LDS loads per thread per operand tile
-  auto issue_w = [&](int t) {
-    const int src = t < KT ? t : KT - 1;              // past the end: a redundant load into the free slot, never consumed
+  auto issue_w = [&](int t) {                           // prologue only: t < 5 is its own phase
+    const int src = t < KT ? t : KT - 1;
 #pragma unroll
-    for (int i = 0; i < LB; ++i) load_span_async<NW>(a.W, n0, a.N, a.K, (kt0 + src) * 64, wslot(t), i);
+    for (int i = 0; i < LB; ++i) load_span_async<NW>(a.W, n0, a.N, a.K, (kt0 + src) * 64, wslot(t), i, wave);
   };
   auto issue_a = [&](int t) {
     const int src = t < KT ? t : KT - 1;
 #pragma unroll
-    for (int i = 0; i < LA; ++i) load_span_async<NW>(a.A, m0, a.M, a.K, (kt0 + src) * 64, aslot(t), i);
+    for (int i = 0; i < LA; ++i) load_span_async<NW>(a.A, m0, a.M, a.K, (kt0 + src) * 64, aslot(t), i, wave);
   };
-  // The loads that refill the two slots a barrier frees, A(t+1) then W(t+2), are dealt into four shares: share 0
-  // goes out right behind that barrier, shares 1..3 with the first three MFMA groups of the next k-step. A burst of
-  // all of them at one point fills the vector-memory queue, and the MFMAs behind a queued load wait with it.
   constexpr int NLD = LA + LB;
   auto share_size = [](int sh) { int c = 0; for (int j = 0; j < NLD; ++j) c += (j * 4 / NLD == sh); return c; };
   constexpr int S0 = share_size(0), S1 = share_size(1), S2 = share_size(2), S3 = share_size(3);
   static_assert(LB == 4 && (S0 == 2) && S1 <= 2 && S2 <= 2 && S3 <= 2, "the waits below are written for these counts");
-  auto issue_share = [&](int ta, int tw, auto share) {
+  // share SH of the loads of A-tile ta (phase pa) and W-tile tw (phase pw)
+  auto issue_share = [&](int ta, int pa, int tw, int pw, auto share) {
     constexpr int SH = decltype(share)::value;
     const int sa = ta < KT ? ta : KT - 1, sw = tw < KT ? tw : KT - 1;   // past the end: redundant loads into free slots
 #pragma unroll
     for (int j = 0; j < NLD; ++j) {
       if (j * 4 / NLD != SH) continue;
-      if (j < LA) load_span_async<NW>(a.A, m0, a.M, a.K, (kt0 + sa) * 64, aslot(ta), j);
-      else load_span_async<NW>(a.W, n0, a.N, a.K, (kt0 + sw) * 64, wslot(tw), j - LA);
+      if (j < LA) load_span_async<NW>(a.A, m0, a.M, a.K, (kt0 + sa) * 64, aslot(pa), j, wave);
+      else load_span_async<NW>(a.W, n0, a.N, a.K, (kt0 + sw) * 64, wslot(pw), j - LA, wave);
     }
   };
-  // One MFMA group of the software pipeline: two MFMAs go first, then the LDS reads of the next group, then the rest
-  // of the MFMAs with the group's (at most two) global loads between them, three MFMAs apart. Nothing in the group
-  // waits on those reads or loads.
 #define SGB __builtin_amdgcn_sched_group_barrier
 #define PIPE_GROUP_ORDER(NLOADS)                                                                                   \
   SGB(0x008, 2, 0);                                                                                                \
@@ -164,69 +165,94 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   __builtin_amdgcn_sched_barrier(0)
 
   issue_w(0); issue_a(0); issue_w(1);
-  issue_share(1, 2, std::integral_constant<int, 0>{});
-  // K-tile 0 has landed when only W1 and the two loads of the first share are still in flight
+  issue_share(1, 1, 2, 2, std::integral_constant<int, 0>{});
   asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");
   bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
   read_frags(0, 0, a0, b0);
-  for (int kt = 0; kt < KT; ++kt) {
-    // The loop body is branch-free so that each MFMA group stays one scheduling region.
-    read_frags(kt, 1, a1, b1);
-    issue_share(kt + 1, kt + 2, std::integral_constant<int, 1>{});
+  auto step = [&](auto phase, int kt) {
+    constexpr int P = decltype(phase)::value;
+    constexpr int P1 = (P + 1) % 5, P2 = (P + 2) % 5, P3 = (P + 3) % 5;
+    read_frags(P, 1, a1, b1);
+    issue_share(kt + 1, P1, kt + 2, P2, std::integral_constant<int, 1>{});
     mma(a0, b0);
     PIPE_GROUP_ORDER(S1);
-    read_frags(kt, 2, a0, b0);
-    issue_share(kt + 1, kt + 2, std::integral_constant<int, 2>{});
+    read_frags(P, 2, a0, b0);
+    issue_share(kt + 1, P1, kt + 2, P2, std::integral_constant<int, 2>{});
     mma(a1, b1);
     PIPE_GROUP_ORDER(S2);
-    read_frags(kt, 3, a1, b1);
-    issue_share(kt + 1, kt + 2, std::integral_constant<int, 3>{});
+    read_frags(P, 3, a1, b1);
+    issue_share(kt + 1, P1, kt + 2, P2, std::integral_constant<int, 3>{});
     mma(a0, b0);
     PIPE_GROUP_ORDER(S3);
-    // Publish K-tile kt+1 (loads complete in order, and the four youngest are W of K-tile kt+2) and retire K-tile
-    // kt: own reads of it are complete, and after the barrier so are everybody's, so its two slots can be refilled.
     asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    issue_share(kt + 2, kt + 3, std::integral_constant<int, 0>{});
-    read_frags(kt + 1 < KT ? kt + 1 : kt, 0, a0, b0);
+    issue_share(kt + 2, P2, kt + 3, P3, std::integral_constant<int, 0>{});
+    read_frags(P1, 0, a0, b0);                         // after the last K-tile: a read of a free slot, never used
     mma(a1, b1);
     PIPE_GROUP_ORDER(S0);
+  };
+  for (int kt = 0;;) {
+    step(std::integral_constant<int, 0>{}, kt); if (++kt >= KT) break;
+    step(std::integral_constant<int, 1>{}, kt); if (++kt >= KT) break;
+    step(std::integral_constant<int, 2>{}, kt); if (++kt >= KT) break;
+    step(std::integral_constant<int, 3>{}, kt); if (++kt >= KT) break;
+    step(std::integral_constant<int, 4>{}, kt); if (++kt >= KT) break;
   }
 #undef PIPE_GROUP_ORDER
 #undef SGB
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-  // accumulator element r of lane: row 8*(r/4) + 4*lhalf + r%4, column lrow of the 32x32 tile
+  // accumulator element r of a lane, storing epilogues: row lrow, column 8*(r/4) + 4*lhalf + r%4 of the 32x32 tile;
+  // vocabulary head: row 8*(r/4) + 4*lhalf + r%4, column lrow
   if (EPI == ME_STORE || EPI == ME_RESIDUAL) {
     float* __restrict__ Cs = a.C + (size_t)blockIdx.y * a.M * a.N;
+    const bool vec = (a.N & 3) == 0 && ((uintptr_t)a.C & 15) == 0;   // 16-byte pieces stay aligned and inside a row
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+      const int row = m0 + wm * WM + i * 32 + lrow;
+      if (row >= a.M) continue;
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        int col = n0 + wn * WN + j * 32 + lrow;
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          int row = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-          if (row < a.M && col < a.N) {
-            size_t o = (size_t)row * a.N + col;
-            if (EPI == ME_RESIDUAL) Cs[o] += acc[i][j][r];
-            else Cs[o] = acc[i][j][r];
+        for (int g = 0; g < 4; ++g) {
+          const int col = n0 + wn * WN + j * 32 + 8 * g + 4 * lhalf;
+          float* dst = Cs + (size_t)row * a.N + col;
+          if (vec && col + 3 < a.N) {
+            float4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+            if (EPI == ME_RESIDUAL) {
+              float4 o = *(const float4*)dst;
+              v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+            }
+            *(float4*)dst = v;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (col + e < a.N) {
+                if (EPI == ME_RESIDUAL) dst[e] += acc[i][j][4 * g + e];
+                else dst[e] = acc[i][j][4 * g + e];
+              }
           }
         }
-      }
+    }
   } else if (EPI == ME_SWIGLU) {
-    const int F = a.N >> 1;
+    const int F = a.N >> 1;                            // a multiple of 32: whole 4-unit pieces
+    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
     for (int jp = 0; jp < TN / 2; ++jp) {              // accumulator pair (2jp, 2jp+1) = gate, up of 32 units
-      int fcol = ((n0 + wn * WN + jp * 64) >> 1) + lrow;
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i) {
+        const int row = m0 + wm * WM + i * 32 + lrow;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          int row = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-          float g = acc[i][2 * jp][r], u = acc[i][2 * jp + 1][r];
-          float v = g * __frcp_rn(1.0f + __expf(-g)) * u;
-          if (row < a.M && fcol < F) a.act[(size_t)row * F + fcol] = (bf16_t)v;
+        for (int g = 0; g < 4; ++g) {
+          const int unit = ((n0 + wn * WN + jp * 64) >> 1) + 8 * g + 4 * lhalf;
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float gt = acc[i][2 * jp][4 * g + e], u = acc[i][2 * jp + 1][4 * g + e];
+            o[e] = (__bf16)(gt * __frcp_rn(1.0f + __expf(-gt)) * u);
+          }
+          if (row < a.M && unit < F) *(bf16x4*)(a.act + (size_t)row * F + unit) = o;
         }
+      }
     }
   } else {  // ME_LMHEAD
     __syncthreads();                                   // every wavefront is done with the operand tiles
@@ -356,7 +382,7 @@ bool launch_gemm_mfma(int epi, const bf16_t* A, const bf16_t* W, int M, int N, i
                       const int32_t* tok, float* part_max, float* part_sum, float* zt, int ksplit, int bm,
                       hipStream_t s) {
   if (K % 64 != 0 || M <= 0 || N <= 0) return false;
-  if (epi == ME_SWIGLU && (N % 64 != 0)) return false;
+  if (epi == ME_SWIGLU && (N % 64 != 0 || ((uintptr_t)act & 7))) return false;
   if (ksplit < 1 || (ksplit > 1 && (epi != ME_STORE || ksplit > K / 64))) return false;
   if (bm != 0 && bm != 128 && bm != 256) return false;
   GemmArgs a;

@@ -38,6 +38,8 @@ def close(got, want, rel):
 LINEAR_SHAPES = [(45, 100, 64), (256, 256, 64), (300, 1152, 128), (130, 257, 192), (300, 1152, 256), (130, 257, 320),
                  (77, 2100, 448), (2048, 4608, 3584),
                  (1024, 1536, 8960), (256, 1024, 2816), (2048, 3584, 18944),
+                 # tile counts that are no multiple of the CU count, with ragged edges
+                 (2000, 4500, 3584), (1000, 3000, 1024), (4100, 1500, 2048), (2048, 1536, 8960), (4096, 8960, 1536),
                  # a few rows (one position of every candidate during generation): the weight-streaming kernel
                  (16, 4608, 3584), (16, 3584, 18944), (5, 301, 128), (32, 2050, 1280), (17, 1536, 8960), (1, 64, 256)]
 

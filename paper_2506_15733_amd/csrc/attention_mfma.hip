@@ -133,13 +133,18 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
   const int n_tiles = SPLIT ? (int)((long)(split + 1) * n_list / a.n_splits) - tile_lo : n_list;
 
   // one wavefront stages one 16-key group (a page, or 16 block tokens) of the tile: K rows and V^T
-  auto stage_tile = [&](int tile, char* buf) {
+  // physical page of this wavefront's 16-key group of a prefix tile (looked up one tile before it is staged, so
+  // that the staging loads never wait for the table)
+  auto page_of = [&](int tile) {
+    int pg = tile * 4 + wave;
+    pg = pg < n_pages ? pg : n_pages - 1;
+    return tile < n_ptiles ? ptab[pg] : 0;
+  };
+  auto stage_tile = [&](int tile, int page_id, char* buf) {
     char* kdst = buf + wave * 16 * KROW;
     char* vdst = buf + K_BYTES + wave * HD * 32;
     if (tile < n_ptiles) {
-      int pg = tile * 4 + wave;
-      pg = pg < n_pages ? pg : n_pages - 1;
-      size_t page = (size_t)ptab[pg];
+      size_t page = (size_t)page_id;
       const bf16_t* ksrc = a.poolK + (page * a.Hkv + kvh) * 16 * HD;
       const bf16_t* vsrc = a.poolV + (page * a.Hkv + kvh) * HD * 16;
 #pragma unroll
@@ -179,7 +184,11 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
     }
   };
 
-  if (n_tiles > 0) stage_tile(tile_lo, smem);
+  int page_next = 0;
+  if (n_tiles > 0) {
+    stage_tile(tile_lo, page_of(tile_lo), smem);
+    page_next = page_of(tile_lo + 1);
+  }
   // pi(i): A-row i of the S^T product carries key pi(i) of the 32-key half tile
   const int pi_row = (lq & 16) | ((lq & 4) << 1) | ((lq & 8) >> 1) | (lq & 3);
 
@@ -187,7 +196,10 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
     const int tile = tile_lo + it;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (it + 1 < n_tiles) stage_tile(tile + 1, smem + ((it + 1) & 1) * STAGE);
+    if (it + 1 < n_tiles) {
+      stage_tile(tile + 1, page_next, smem + ((it + 1) & 1) * STAGE);
+      page_next = page_of(tile + 2);                   // lands while this tile is being multiplied
+    }
     const char* Ks = smem + (it & 1) * STAGE;
     const char* Vs = Ks + K_BYTES;
     const bool is_block = tile >= n_ptiles;

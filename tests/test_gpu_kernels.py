@@ -183,10 +183,13 @@ def test_attention_f32_ragged(ctx):
     (12, 2, 128, 2, 3, 64, [333, 1000], 16),         # ragged prefix lengths, group of 6
     (28, 4, 128, 1, 16, 128, [4096], 16),            # config-4 shape (sampled candidates)
     (14, 2, 64, 1, 2, 70, [100], 16),                # block length not a multiple of any tile
+    (12, 2, 128, 2, 3, 64, [1, 17], 16),             # prefixes shorter than a key tile: one and two pages
+    (8, 8, 64, 3, 2, 16, [64, 65, 127], 16),         # prefix ends on, just after and just before a tile boundary
 ])
 def test_attention_bf16(ctx, Hq, Hkv, hd, Bn, n, L, lens, pt):
     d = ModelDesc("target", 1, Hq * hd, Hq, Hkv, hd, 64, 64, "bf16", "lm")
     sample = None if Bn * n <= 8 else [0, 7, Bn * n - 1]
     err = attention_case(ctx, d, Bn, n, L, lens, pt, sample)
-    # outputs are O(1) averages of unit normals rounded to bf16: one bf16 ulp of the largest plausible value
-    assert err < 2.0 ** -7, err
+    # outputs are averages of unit normals rounded to bf16: one bf16 ulp of the largest plausible value, which is
+    # below 2 when hundreds of keys are averaged and below 4 when a row sees only two or three keys
+    assert err < 2.0 ** -7 or (min(lens) < 64 and err <= 2.0 ** -6), err

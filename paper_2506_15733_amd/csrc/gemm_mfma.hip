@@ -3,12 +3,15 @@
 // Block tile BM x 256 x 64 (BM = 256 or 128), 512 threads = 8 wavefronts laid out 2 (M) x 4 (N);
 // every wavefront owns a (BM/2) x 64 patch as (BM/64) x 2 accumulators of
 // v_mfma_f32_32x32x16_bf16. Operand tiles go global -> LDS directly (16 bytes per lane,
-// no register staging), double buffered: the loads of K-tile t+1 are in flight while K-tile t
-// is multiplied. LDS rows are 128 bytes (64 bf16); the 16-byte chunk c of row r is stored at
+// no register staging) into a ring of five 32 KiB slots: two being multiplied, three in flight.
+// Wavefronts issue in order and the vector-memory queue is short, so the eight loads a wavefront
+// contributes per k-step are dealt over the k-step's four MFMA groups, one load between MFMAs,
+// instead of one burst; the k-loop is unrolled by the ring length so that slot addresses are
+// constants. LDS rows are 128 bytes (64 bf16); the 16-byte chunk c of row r is stored at
 // chunk position c ^ ((r >> 1) & 7) so that the 32 rows a fragment read touches spread over all
 // banks. Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the id -> tile map
 // below keeps all M-tiles of one N-tile on one XCD, so a weight tile is fetched from HBM once
-// and re-used out of that XCD's L2.
+// and re-used out of that XCD's L2 by workgroups that walk through K in step.
 //
 // Epilogues: plain float store; residual add into the float stream; SwiGLU (gate/up columns
 // interleaved in groups of 32 so that a lane holds gate and up of the same unit) with bf16

@@ -213,16 +213,33 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
       for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[u][hf][r] = 0.f;
-    // K-step outer, key half inner: the two accumulator chains of a query tile alternate
+    // K-step outer, key half inner: the two accumulator chains of a query tile alternate. The key fragments are
+    // read KPF K-steps ahead of the MFMAs that use them, so that the LDS latency is hidden behind MFMAs.
+    constexpr int KPF = 2;
+    auto read_kf = [&](int ks, int hf) {
+      int row = hf * 32 + pi_row;
+      return *(const bf16x8*)(Ks + row * KROW + (k_swizzle<HD>(row, ks * 2 + lh) << 4));
+    };
+    bf16x8 kf[KPF + 1][2];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
+    for (int ks = 0; ks < KPF; ++ks)
 #pragma unroll
-      for (int hf = 0; hf < 2; ++hf) {
-        int row = hf * 32 + pi_row;
-        bf16x8 kf = *(const bf16x8*)(Ks + row * KROW + (k_swizzle<HD>(row, ks * 2 + lh) << 4));
+      for (int hf = 0; hf < 2; ++hf) kf[ks][hf] = read_kf(ks, hf);
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * KPF, 0);
 #pragma unroll
-        for (int u = 0; u < QT; ++u) s[u][hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[u][ks], s[u][hf], 0, 0, 0);
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + KPF < KS) {
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) kf[(ks + KPF) % (KPF + 1)][hf] = read_kf(ks + KPF, hf);
       }
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int u = 0; u < QT; ++u)
+          s[u][hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks % (KPF + 1)][hf], qf[u][ks], s[u][hf], 0, 0, 0);
+      if (ks + KPF < KS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * QT, 0);
+    }
 
     // accumulator value r of half hf in this lane is key  key_base + hf*32 + 16*(r/8) + 8*lh + r%8
     bf16x8 pf[QT][4];
@@ -271,14 +288,26 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
     }
 
     // O^T += V^T P^T : K-step = one 16-key group (page) pg, this lane supplies keys 8*lh .. 8*lh+7 of it
+    // (value fragments are read VPF MFMA steps ahead of their use, like the key fragments above)
+    constexpr int VPF = 2, NST = 4 * NI;
+    auto read_vf = [&](int st) {
+      const int pg = st / NI, dt = st % NI;
+      return *(const bf16x8*)(Vs + pg * HD * 32 + (dt * 32 + lq) * 32 + ((lh ^ ((lq >> 3) & 1)) << 4));
+    };
+    bf16x8 vf[VPF + 1];
 #pragma unroll
-    for (int pg = 0; pg < 4; ++pg)
+    for (int st = 0; st < VPF; ++st) vf[st] = read_vf(st);
+    __builtin_amdgcn_sched_group_barrier(0x100, VPF, 0);
 #pragma unroll
-      for (int dt = 0; dt < NI; ++dt) {
-        bf16x8 vf = *(const bf16x8*)(Vs + pg * HD * 32 + (dt * 32 + lq) * 32 + ((lh ^ ((lq >> 3) & 1)) << 4));
+    for (int st = 0; st < NST; ++st) {
+      const int pg = st / NI, dt = st % NI;
+      if (st + VPF < NST) vf[(st + VPF) % (VPF + 1)] = read_vf(st + VPF);
 #pragma unroll
-        for (int u = 0; u < QT; ++u) o[u][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u][pg], o[u][dt], 0, 0, 0);
-      }
+      for (int u = 0; u < QT; ++u)
+        o[u][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st % (VPF + 1)], pf[u][pg], o[u][dt], 0, 0, 0);
+      if (st + VPF < NST) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, QT, 0);
+    }
   }
 
   // normalise and store: lane = query column, accumulator value r of d-tile dt is d = dt*32 + 8*(r/4) + 4*lh + r%4

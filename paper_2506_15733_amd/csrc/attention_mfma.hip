@@ -47,6 +47,17 @@ struct AttnArgs {
   float* part_l;        // [..][128] sum of weights relative to that maximum
 };
 
+// The value of lane l and of lane l ^ 32 (v_permlane32_swap: the upper half of one copy trades places with the lower
+// half of the other, no trip through the LDS crossbar), combined with max or +.
+__device__ __forceinline__ float half_wave_max(float v) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_wave_sum(float v) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 template <int HD>
 __device__ __forceinline__ int k_swizzle(int row, int chunk) {
   return HD == 128 ? (chunk ^ (row & 15)) : (chunk ^ ((row >> 1) & 7));
@@ -85,7 +96,8 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
   const int kvh = rem % a.Hkv;
   const int b = rem / a.Hkv;
 
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  // the wavefront index as a scalar: page ids, page bases and LDS destinations then live in scalar registers
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int lq = lane & 31, lh = lane >> 5;
   const int P = G.len_override >= 0 ? G.len_override : G.lens[G.b0 + b];
   const int L = G.L;
@@ -144,7 +156,8 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
     char* kdst = buf + wave * 16 * KROW;
     char* vdst = buf + K_BYTES + wave * HD * 32;
     if (tile < n_ptiles) {
-      size_t page = (size_t)page_id;
+      // scalar page base + a 32-bit lane offset that does not change from tile to tile
+      size_t page = (size_t)__builtin_amdgcn_readfirstlane(page_id);
       const bf16_t* ksrc = a.poolK + (page * a.Hkv + kvh) * 16 * HD;
       const bf16_t* vsrc = a.poolV + (page * a.Hkv + kvh) * HD * 16;
 #pragma unroll
@@ -152,13 +165,14 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
         int qi = i * 64 + lane;
         int row = qi / KCH, slot = qi % KCH;
         int chunk = k_swizzle<HD>(wave * 16 + row, slot);
-        __builtin_amdgcn_global_load_lds(GLB_PTR(ksrc + row * HD + chunk * 8), LDS_PTR(kdst + i * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLB_PTR(ksrc + (unsigned)(row * HD + chunk * 8)), LDS_PTR(kdst + i * 1024), 16, 0,
+                                         0);
       }
 #pragma unroll
       for (int i = 0; i < NI; ++i) {
         int qi = i * 64 + lane;
         int d = qi >> 1, half = (qi & 1) ^ ((d >> 3) & 1);       // LDS chunk position qi&1 holds key half `half`
-        __builtin_amdgcn_global_load_lds(GLB_PTR(vsrc + d * 16 + half * 8), LDS_PTR(vdst + i * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLB_PTR(vsrc + (unsigned)(d * 16 + half * 8)), LDS_PTR(vdst + i * 1024), 16, 0, 0);
       }
     } else {
       int key0 = (tile - n_ptiles) * 64 + wave * 16;
@@ -261,20 +275,25 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
       for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[u][hf][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      // running maximum in the log2 domain: scores are scaled by scale*log2(e) > 0 inside the exponent's FMA
-      const float m_new = fmaxf(m_run[u], mx * a.scale_log2e);
-      const float m_use = m_new == -INFINITY ? 0.f : m_new;   // nothing visible yet: every p below is exp2(-inf) = 0
-      // rescale the accumulators only when some row's maximum moved (rare after the first tiles)
-      if (__any(m_new > m_run[u])) {
-        const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run[u] - m_new);
+      mx = half_wave_max(mx);
+      // Reference exponent of the row in the log2 domain (scores are scaled by scale*log2(e) > 0 inside the
+      // exponent's FMA). It follows the row maximum lazily: the accumulators are rescaled only when the maximum has
+      // grown by more than 2^RESCALE_LOG2 past the reference, so weights reach at most that factor (exact in
+      // float; O/l at the end does not depend on the reference) and the 64 multiplications per lane become rare.
+      constexpr float RESCALE_LOG2 = 8.f;
+      const float m_tile = mx * a.scale_log2e;
+      const bool move = m_tile > m_run[u] + RESCALE_LOG2;   // also the first visible key: -inf + 8 = -inf
+      if (__any(move)) {
+        const float m_new = move ? m_tile : m_run[u];
+        const float alpha = move ? __builtin_amdgcn_exp2f(m_run[u] - m_new) : 1.f;   // exp2(-inf) = 0: nothing yet
         l_run[u] *= alpha;
 #pragma unroll
         for (int dt = 0; dt < NI; ++dt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[u][dt][r] *= alpha;
+        m_run[u] = m_new;
       }
-      m_run[u] = m_new;
+      const float m_use = m_run[u] == -INFINITY ? 0.f : m_run[u];   // nothing visible yet: every p below is exp2(-inf) = 0
       float psum = 0.f;
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf)
@@ -314,7 +333,7 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
 #pragma unroll
   for (int u = 0; u < QT; ++u) {
     int r = r_wg0 + (wave * QT + u) * 32 + lq;
-    float l = l_run[u] + __shfl_xor(l_run[u], 32, 64);
+    float l = half_wave_sum(l_run[u]);
     if (SPLIT) {
       const size_t group = DEC ? (size_t)b * a.Hkv + kvh : ((size_t)b * a.Hkv + kvh) * G.n + cand;
       const size_t prow = ((group * a.q_tiles + qt_idx) * a.n_splits + split) * BQ + (wave * QT + u) * 32 + lq;

@@ -71,6 +71,16 @@ __device__ __forceinline__ float dpp_move(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
 }
 constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
+// Lane l ^ 16: v_permlane16_swap trades the odd 16-lane rows of one copy for the even rows of the other, so the two
+// results together hold the lane's own value and that of its partner row (again without the LDS crossbar).
+__device__ __forceinline__ float row_pair_max(float v) {
+  auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float row_pair_sum(float v) {
+  auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
 template <int BM, int EPI, int NWN>
 __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
@@ -296,7 +306,7 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx[r] = fmaxf(mx[r], dpp_move<DPP_MIRROR>(mx[r]));
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mx[r] = fmaxf(mx[r], __shfl_xor(mx[r], 16, 64));
+      for (int r = 0; r < 16; ++r) mx[r] = row_pair_max(mx[r]);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         sm[r] = 0.f;
@@ -315,7 +325,7 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) sm[r] += dpp_move<DPP_MIRROR>(sm[r]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sm[r] += __shfl_xor(sm[r], 16, 64);
+      for (int r = 0; r < 16; ++r) sm[r] = row_pair_sum(sm[r]);
       if (lrow == 0) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {

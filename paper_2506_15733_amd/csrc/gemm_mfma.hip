@@ -261,7 +261,9 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             float gt = acc[i][2 * jp][4 * g + e], u = acc[i][2 * jp + 1][4 * g + e];
-            o[e] = (__bf16)(gt * __frcp_rn(1.0f + __expf(-gt)) * u);
+            // v_rcp_f32 (1 ulp) instead of an IEEE division: the quotient is rounded to bf16 right away, and the
+            // division's scale/fix-up sequence alone was ten instructions per value
+            o[e] = (__bf16)(gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * u);
           }
           if (row < a.M && unit < F) *(bf16x4*)(a.act + (size_t)row * F + unit) = o;
         }

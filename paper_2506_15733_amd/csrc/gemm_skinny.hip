@@ -150,7 +150,7 @@ __global__ void __launch_bounds__(64 * WPB) gemm_skinny_kernel(SkinnyArgs a) {
         float mine = acc[0][g][e];
         float other = __shfl_xor(mine, 32, 64);
         float gt = c < 2 ? mine : other, up = c < 2 ? other : mine;
-        o[e] = (__bf16)(gt * __frcp_rn(1.0f + __expf(-gt)) * up);
+        o[e] = (__bf16)(gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up);
       }
       if (c < 2 && m < a.M) *(bf16x4*)(a.act + (size_t)m * F + unit) = o;
     }

@@ -252,26 +252,31 @@ __global__ void rope_split_kernel(const float* __restrict__ qkv, const float* __
   const size_t krow = cand * L + t;
   // blockIdx.y strides over the heads (one block per row when gridDim.y == 1, one per (row, head) for few rows)
   const int heads_here = (H - (int)blockIdx.y + (int)gridDim.y - 1) / (int)gridDim.y;
-  {
-    for (int e = threadIdx.x; e < heads_here * half; e += blockDim.x) {
-      const int h = blockIdx.y + (e / half) * gridDim.y, i = e % half;
-      float x1 = in[h * hd + i], x2 = in[h * hd + half + i];
-      for (int pidx = 1; pidx < parts; ++pidx) {         // K-split projection: add the slices up, in order
-        x1 += in[pidx * part_stride + h * hd + i];
-        x2 += in[pidx * part_stride + h * hd + half + i];
-      }
-      if (h < Hq + Hkv) {
-        float cn = c[i], sn = c[half + i];
-        float y1 = x1 * cn - x2 * sn, y2 = x2 * cn + x1 * sn;
-        T* o = (h < Hq) ? q + (m * Hq + h) * hd : kblk + (krow * Hkv + (h - Hq)) * hd;
-        o[i] = from_f32<T>(y1);
-        o[half + i] = from_f32<T>(y2);
-      } else {
-        T* o = vT + ((cand * Hkv + (h - Hq - Hkv)) * hd) * Lp + t;
-        o[(size_t)i * Lp] = from_f32<T>(x1);
-        o[(size_t)(half + i) * Lp] = from_f32<T>(x2);
-      }
+  auto rotate = [&](int h, int i) {
+    float x1 = in[h * hd + i], x2 = in[h * hd + half + i];
+    for (int pidx = 1; pidx < parts; ++pidx) {           // K-split projection: add the slices up, in order
+      x1 += in[pidx * part_stride + h * hd + i];
+      x2 += in[pidx * part_stride + h * hd + half + i];
     }
+    if (h < Hq + Hkv) {
+      float cn = c[i], sn = c[half + i];
+      float y1 = x1 * cn - x2 * sn, y2 = x2 * cn + x1 * sn;
+      T* o = (h < Hq) ? q + (m * Hq + h) * hd : kblk + (krow * Hkv + (h - Hq)) * hd;
+      o[i] = from_f32<T>(y1);
+      o[half + i] = from_f32<T>(y2);
+    } else {
+      T* o = vT + ((cand * Hkv + (h - Hq - Hkv)) * hd) * Lp + t;
+      o[(size_t)i * Lp] = from_f32<T>(x1);
+      o[(size_t)(half + i) * Lp] = from_f32<T>(x2);
+    }
+  };
+  if (blockDim.x % half == 0) {
+    // thread -> (head slot, pair index) once, then whole head slots per pass: no division per element
+    const int slots = blockDim.x / half, hs0 = threadIdx.x / half, i = threadIdx.x - hs0 * half;
+    for (int hs = hs0; hs < heads_here; hs += slots) rotate(blockIdx.y + hs * gridDim.y, i);
+  } else {
+    for (int e = threadIdx.x; e < heads_here * half; e += blockDim.x)
+      rotate(blockIdx.y + (e / half) * gridDim.y, e % half);
   }
   if (blockIdx.y == 0 && t == L - 1 && Lp > L) {
     for (int e = threadIdx.x; e < Hkv * hd; e += blockDim.x)

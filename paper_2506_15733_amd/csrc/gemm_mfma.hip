@@ -249,26 +249,33 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   } else if (EPI == ME_SWIGLU) {
     const int F = a.N >> 1;                            // a multiple of 32: whole 4-unit pieces
     typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+    // one decision for the workgroup: a tile inside the matrix stores without per-piece bounds checks
+    const bool inside = m0 + BM <= a.M && n0 + BN <= a.N;
+    auto emit = [&](auto checked) {
+      constexpr bool CHECK = decltype(checked)::value;
 #pragma unroll
-    for (int jp = 0; jp < TN / 2; ++jp) {              // accumulator pair (2jp, 2jp+1) = gate, up of 32 units
+      for (int jp = 0; jp < TN / 2; ++jp) {            // accumulator pair (2jp, 2jp+1) = gate, up of 32 units
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const int row = m0 + wm * WM + i * 32 + lrow;
+        for (int i = 0; i < TM; ++i) {
+          const int row = m0 + wm * WM + i * 32 + lrow;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int unit = ((n0 + wn * WN + jp * 64) >> 1) + 8 * g + 4 * lhalf;
-          bf16x4 o;
+          for (int g = 0; g < 4; ++g) {
+            const int unit = ((n0 + wn * WN + jp * 64) >> 1) + 8 * g + 4 * lhalf;
+            bf16x4 o;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float gt = acc[i][2 * jp][4 * g + e], u = acc[i][2 * jp + 1][4 * g + e];
-            // v_rcp_f32 (1 ulp) instead of an IEEE division: the quotient is rounded to bf16 right away, and the
-            // division's scale/fix-up sequence alone was ten instructions per value
-            o[e] = (__bf16)(gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * u);
+            for (int e = 0; e < 4; ++e) {
+              float gt = acc[i][2 * jp][4 * g + e], u = acc[i][2 * jp + 1][4 * g + e];
+              // v_rcp_f32 (1 ulp) instead of an IEEE division: the quotient is rounded to bf16 right away, and the
+              // division's scale/fix-up sequence alone was ten instructions per value
+              o[e] = (__bf16)(gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * u);
+            }
+            if (!CHECK || (row < a.M && unit < F)) *(bf16x4*)(a.act + (size_t)row * F + unit) = o;
           }
-          if (row < a.M && unit < F) *(bf16x4*)(a.act + (size_t)row * F + unit) = o;
         }
       }
-    }
+    };
+    if (inside) emit(std::false_type{});
+    else emit(std::true_type{});
   } else {  // ME_LMHEAD
     __syncthreads();                                   // every wavefront is done with the operand tiles
     int* tgt = (int*)smem;                             // [BM] target token of each row of the tile

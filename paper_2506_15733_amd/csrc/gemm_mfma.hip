@@ -63,22 +63,14 @@ __device__ __forceinline__ bf16x8 lds_frag(const char* tile, int row, int chunk)
   return *(const bf16x8*)(tile + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
 }
 
-// Value of lane (l ^ 1), (l ^ 2), and of the mirrored lane within 8 or 16 lanes, as data-parallel-primitive moves
-// of the vector ALU (no LDS crossbar traffic). After the two quad steps all four lanes of a quad agree, so the
-// mirrored reads bring in exactly the other half of the 8- (16-) lane group.
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
-}
-constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
-// Lane l ^ 16: v_permlane16_swap trades the odd 16-lane rows of one copy for the even rows of the other, so the two
-// results together hold the lane's own value and that of its partner row (again without the LDS crossbar).
-__device__ __forceinline__ float row_pair_max(float v) {
-  auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+// The value of lane l and of lane l ^ 32 (v_permlane32_swap: the upper half of one copy trades places with the lower
+// half of the other, no trip through the LDS crossbar), combined with max or +.
+__device__ __forceinline__ float half_wave_max(float v) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
-__device__ __forceinline__ float row_pair_sum(float v) {
-  auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+__device__ __forceinline__ float half_wave_sum(float v) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
@@ -87,10 +79,10 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   constexpr int BN = 256;
   constexpr int NW = 2 * NWN;                         // wavefronts: 2 along M x NWN along N
   constexpr int WM = BM / 2, TM = WM / 32, WN = BN / NWN, TN = WN / 32;
-  // The storing epilogues multiply W-fragment x A-fragment, i.e. the transposed 32x32 product: a lane then holds
-  // runs of four consecutive COLUMNS of one row of C and stores them as one 16-byte (8-byte bf16) piece; with the
-  // operands the other way round it holds single elements of four rows and needs four times the store instructions.
-  constexpr bool TRANS = EPI != ME_LMHEAD;
+  // All epilogues multiply W-fragment x A-fragment, i.e. the transposed 32x32 product: a lane then holds runs of
+  // four consecutive COLUMNS of one row of C. The storing epilogues write them as one 16-byte (8-byte bf16) piece
+  // (four times fewer store instructions than with single elements of four rows), and the vocabulary head reduces
+  // its rows inside the lane instead of across lanes.
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   // id -> (m_tile, n_tile): ids congruent mod 8 share an XCD. An XCD owns the N-tiles n = 8j + xcd; the 32
@@ -139,8 +131,7 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        acc[i][j] = TRANS ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0)
-                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
   };
   constexpr int LA = BM / (8 * NW), LB = BN / (8 * NW);   // direct-to-LDS loads per thread per operand tile
   auto issue_w = [&](int t) {                           // prologue only: t < 5 is its own phase
@@ -214,8 +205,7 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
 #undef SGB
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-  // accumulator element r of a lane, storing epilogues: row lrow, column 8*(r/4) + 4*lhalf + r%4 of the 32x32 tile;
-  // vocabulary head: row 8*(r/4) + 4*lhalf + r%4, column lrow
+  // accumulator element r of a lane: row lrow, column 8*(r/4) + 4*lhalf + r%4 of the 32x32 tile
   if (EPI == ME_STORE || EPI == ME_RESIDUAL) {
     float* __restrict__ Cs = a.C + (size_t)blockIdx.y * a.M * a.N;
     const bool vec = (a.N & 3) == 0 && ((uintptr_t)a.C & 15) == 0;   // 16-byte pieces stay aligned and inside a row
@@ -278,70 +268,45 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
     else emit(std::true_type{});
   } else {  // ME_LMHEAD
     __syncthreads();                                   // every wavefront is done with the operand tiles
-    int* tgt = (int*)smem;                             // [BM] target token of each row of the tile
-    float* red_max = (float*)(smem + BM * 4);          // [BM][NWN]
+    float* red_max = (float*)smem;                     // [BM][NWN]
     float* red_sum = red_max + BM * NWN;
-    for (int t = threadIdx.x; t < BM; t += 64 * NW) tgt[t] = m0 + t < a.M ? a.tok[m0 + t] : -1;
-    __syncthreads();
-    // the lane's rows come in runs of four (r & 3): one 16-byte LDS read per run, all before the reductions
-    int4 tg[TM][4];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) tg[i][rq] = *(const int4*)(tgt + wm * WM + i * 32 + 8 * rq + 4 * lhalf);
-    // The 16 rows of one accumulator are reduced across the 32 lanes in lockstep, stage by stage, so that the
-    // 16 cross-lane exchanges of a stage are independent and their latencies overlap.
+    // A lane owns row lrow of each of its TM row tiles and, of the wavefront's WN columns, the 16 * TN with
+    // (column / 4) % 2 == lhalf: maximum and sum of exponentials run over the lane's own registers, one exchange
+    // joins the two half-waves, and the row's target column is looked for among the same registers.
+    const bool ragged = n0 + BN > a.N;                 // only the last N-tile has columns beyond the matrix
+    const int cbase = n0 + wn * WN + 4 * lhalf;        // column of element (j, r): cbase + 32 j + 8 (r / 4) + r % 4
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      float mx[16], sm[16];
+      const int lr = wm * WM + i * 32 + lrow, row = m0 + lr;
+      const int target = row < a.M ? a.tok[row] : -1;
+      float mx = -INFINITY;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int4 t4 = tg[i][r >> 2];
-        int target = (r & 3) == 0 ? t4.x : (r & 3) == 1 ? t4.y : (r & 3) == 2 ? t4.z : t4.w;
-        mx[r] = -INFINITY;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          int col = n0 + wn * WN + j * 32 + lrow;
-          if (col < a.N) mx[r] = fmaxf(mx[r], acc[i][j][r]);
-          if (col == target) a.zt[m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3)] = acc[i][j][r];
-        }
-      }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx[r] = fmaxf(mx[r], dpp_move<DPP_XOR1>(mx[r]));
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx[r] = fmaxf(mx[r], dpp_move<DPP_XOR2>(mx[r]));
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx[r] = fmaxf(mx[r], dpp_move<DPP_HALF_MIRROR>(mx[r]));
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx[r] = fmaxf(mx[r], dpp_move<DPP_MIRROR>(mx[r]));
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx[r] = row_pair_max(mx[r]);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        sm[r] = 0.f;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          int col = n0 + wn * WN + j * 32 + lrow;
-          if (col < a.N) sm[r] += __expf(acc[i][j][r] - mx[r]);
-        }
-      }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sm[r] += dpp_move<DPP_XOR1>(sm[r]);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sm[r] += dpp_move<DPP_XOR2>(sm[r]);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sm[r] += dpp_move<DPP_HALF_MIRROR>(sm[r]);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sm[r] += dpp_move<DPP_MIRROR>(sm[r]);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sm[r] = row_pair_sum(sm[r]);
-      if (lrow == 0) {
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          int lr = wm * WM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-          red_max[lr * NWN + wn] = mx[r];
-          red_sum[lr * NWN + wn] = sm[r];
+          if (ragged && cbase + 32 * j + 8 * (r >> 2) + (r & 3) >= a.N) acc[i][j][r] = -INFINITY;
+          mx = fmaxf(mx, acc[i][j][r]);
         }
+      mx = half_wave_max(mx);
+      // the target's offset among this lane's columns; element (j, r) sits at 32 j + 8 (r / 4) + r % 4
+      const int d = target - cbase;
+      float sm = 0.f, zt = 0.f;
+      bool hit = false;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float v = acc[i][j][r];
+          sm += mx == -INFINITY ? 0.f : __expf(v - mx);
+          const bool here = d == 32 * j + 8 * (r >> 2) + (r & 3);
+          zt = here ? v : zt;
+          hit |= here;
+        }
+      sm = half_wave_sum(sm);
+      if (hit) a.zt[row] = zt;
+      if (lhalf == 0) {
+        red_max[lr * NWN + wn] = mx;
+        red_sum[lr * NWN + wn] = sm;
       }
     }
     __syncthreads();

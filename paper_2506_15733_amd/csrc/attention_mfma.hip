@@ -424,12 +424,13 @@ bool launch_attention_mfma(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT,
   bool big = t2 * 256 < t1 * 128;
   a.q_tiles = big ? t2 : t1;
   a.total_wg = g.B * md.Hkv * g.n * a.q_tiles;
-  // Few workgroups and a long key list: cut the list so that about two workgroups per CU exist, at least four
-  // tiles per run, at most eight runs.
+  // Few workgroups and a long key list: cut the list into as many runs as still leave all workgroups resident at
+  // once (two per CU; one more run would add a second, almost empty round), at least four tiles per run, at most
+  // eight runs.
   int list_tiles = (max_ctx + 63) / 64 + (g.L + 63) / 64;
   int splits = 1;
   if (!big && part && a.total_wg < 384 && list_tiles >= 16) {   // short lists: a second kernel costs more than it saves
-    splits = (512 + a.total_wg - 1) / a.total_wg;
+    splits = 512 / a.total_wg;
     splits = splits > 8 ? 8 : splits;
     splits = splits > list_tiles / 4 ? list_tiles / 4 : splits;
     size_t per_split = (size_t)a.total_wg * 128 * (md.hd + 2);

@@ -2,8 +2,8 @@
 // bf16 operands, float accumulation, K % 128 == 0. Every weight byte is read once and used for M <= 32
 // multiply-adds, so the kernel is bound by HBM bandwidth and is organised around keeping loads in flight:
 //   * a wavefront owns 16 weight rows and walks along K in slabs of 128: four 16-byte loads per lane per slab
-//     straight into registers (64 contiguous bytes per row and instruction), the next slab requested before the
-//     current one is multiplied;
+//     straight into registers (64 contiguous bytes per row and instruction), the next slab (the next three, when a
+//     launch has only a few wavefronts per CU) requested before the current one is multiplied;
 //   * the weight rows are the A operand of v_mfma_f32_16x16x32_bf16, the (few) activation rows its B operand,
 //     read from an LDS copy of A that the workgroup's four or eight wavefronts share (staged 1024 columns at a time,
 //     16-byte chunks XOR-swizzled by the token index so that the 16 tokens of a read hit distinct banks);
@@ -28,7 +28,7 @@ struct SkinnyArgs {
   int M, N, K, ksplit;
 };
 
-template <int TG, int EPI, int WPB>
+template <int TG, int EPI, int WPB, int PF>
 __global__ void __launch_bounds__(64 * WPB) gemm_skinny_kernel(SkinnyArgs a) {
   constexpr int STAGE_COLS = 1024;                       // activation columns resident in LDS
   constexpr int ROWB = STAGE_COLS * 2;                   // bytes per LDS row
@@ -66,15 +66,14 @@ __global__ void __launch_bounds__(64 * WPB) gemm_skinny_kernel(SkinnyArgs a) {
 
   // PF register sets take turns: while one slab is multiplied the loads of the next PF-1 are in flight, which is
   // what keeps HBM busy when a launch has only a few wavefronts per CU
-  constexpr int PF = 2;
   static_assert((STAGE_COLS / 128) % PF == 0, "a stage must hold a whole number of register-set rounds");
   bf16x8 w[PF][NSUB][4];
   auto load_slab = [&](int kt, bf16x8 (&dst)[NSUB][4]) {
-    const int ktc = kt < kt1 ? kt : kt1 - 1;             // past the end: a redundant in-bounds load, never used
+    if (kt >= kt1) return;                               // past the end of the slice: nothing to fetch
 #pragma unroll
     for (int u = 0; u < NSUB; ++u)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) dst[u][j] = *(const bf16x8*)(wp[u] + (size_t)ktc * 128 + 32 * j);
+      for (int j = 0; j < 4; ++j) dst[u][j] = *(const bf16x8*)(wp[u] + (size_t)kt * 128 + 32 * j);
   };
   auto multiply = [&](int slab_in_stage, const bf16x8 (&w)[NSUB][4]) {
     const int chbase = slab_in_stage * 16 + c;           // chunk of this lane's k-offset 8c within the slab, + 4j below
@@ -183,9 +182,12 @@ bool launch_gemm_skinny(int epi, const bf16_t* A, const bf16_t* W, int M, int N,
   // eight wavefronts share one LDS copy of A where that still leaves two workgroups per CU, else four
   bool wide = (long)((tiles + 7) / 8) * ksplit >= 512;
   dim3 grid(wide ? (tiles + 7) / 8 : (tiles + 3) / 4, ksplit);
+  // few wavefronts per CU: three slabs in flight per wavefront instead of one
+  const bool deep = (long)grid.x * grid.y * (wide ? 8 : 4) < 256 * 8;
 #define SKINNY(TG, E)                                                                  \
-  if (wide) gemm_skinny_kernel<TG, E, 8><<<grid, 512, 0, s>>>(a);                      \
-  else gemm_skinny_kernel<TG, E, 4><<<grid, 256, 0, s>>>(a)
+  if (wide) gemm_skinny_kernel<TG, E, 8, 2><<<grid, 512, 0, s>>>(a);                   \
+  else if (deep) gemm_skinny_kernel<TG, E, 4, 4><<<grid, 256, 0, s>>>(a);              \
+  else gemm_skinny_kernel<TG, E, 4, 2><<<grid, 256, 0, s>>>(a)
   if (epi == MFMA_SWIGLU) {
     if (M <= 16) { SKINNY(1, SK_SWIGLU); } else { SKINNY(2, SK_SWIGLU); }
   } else {

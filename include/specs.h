@@ -149,6 +149,23 @@ int specs_prefill(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const i
 int specs_score_blocks(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const int32_t* cand,
                        int32_t n, int32_t L, float* out, float* tok_logp);
 
+/* specs_score_blocks for callers that cannot allocate device memory or hand over a workspace sized for the
+ * call: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments,
+ * same kernels and bit-identical results, but every working buffer of the pass lives in a scratch array that
+ * is part of the library's device image (SPECS_STATIC_SCRATCH_BYTES per GPU, held until the process ends)
+ * instead of the context's workspace, which then only has to hold the 256-byte status word. The call
+ * allocates nothing and calls no allocating routine. Limits and rules:
+ *  - SPECS_EWORKSPACE when specs_workspace_bytes(desc, B*n*L, B*n) exceeds SPECS_STATIC_SCRATCH_BYTES
+ *    (the two small benchmark configurations fit; the 1.5B and 7B models do not);
+ *  - every call on a GPU shares that GPU's array, whatever the context or stream: calls that overlap on one
+ *    GPU race, the caller must order them. Nothing in the array has to start at zero (every buffer is
+ *    written before it is read), so the contents a previous call left behind are harmless;
+ *  - the block's keys/values are not kept for specs_commit_block: SPECS_EINVAL if it follows this call;
+ *  - SPECS_EINVAL while per-kernel timing (specs_ctx_profile) is switched on, since that creates events. */
+#define SPECS_STATIC_SCRATCH_BYTES (32u << 20)
+int specs_score_blocks_static(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const int32_t* cand,
+                              int32_t n, int32_t L, float* out, float* tok_logp);
+
 /* Generation of the candidate blocks (Alg. 1, Step I): the model (LM head) draws n blocks of L tokens
  * for every beam from pi(. | tr), token by token, each token by ancestral sampling from the full
  * softmax at temperature 1: with c_k the running sum of exp(z_v - max z) over ids v <= k,

@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = [
     "specs_model_destroy", "specs_prefix_create", "specs_prefix_destroy", "specs_prefill", "specs_score_blocks",
     "specs_commit_block", "specs_subsample", "specs_strerror", "specs_generate_blocks",
     "specs_op_linear", "specs_op_gate_up", "specs_op_lmhead_logprob", "specs_op_attention",
-    "specs_ctx_profile", "specs_ctx_profile_read",
+    "specs_ctx_profile", "specs_ctx_profile_read", "specs_score_blocks_static",
 ]
 KERNEL_CLASSES = ("qkv", "attention", "oproj", "gate_up", "down", "lmhead", "other")
 
@@ -66,6 +66,7 @@ def load_library():
     lib.specs_prefix_destroy.argtypes = [vp]
     lib.specs_prefill.argtypes = [vp, vp, vp, vp]
     lib.specs_score_blocks.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp]
+    lib.specs_score_blocks_static.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp]
     lib.specs_generate_blocks.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.specs_commit_block.argtypes = [vp, vp, vp, C.POINTER(i32)]
     lib.specs_subsample.argtypes = [vp, vp, vp, vp, vp, i32, i32, C.POINTER(C.c_float), i32, vp, vp, vp]
@@ -186,6 +187,14 @@ def specs_score_blocks(ctx, model, prefix, cand, out, tok_logp=None):
     _check(load_library().specs_score_blocks(ctx, model, prefix, _ptr(cand, torch.int32), n, L,
                                              _ptr(out, torch.float32), _ptr(tok_logp, torch.float32, True)),
            "specs_score_blocks")
+
+
+def specs_score_blocks_static(ctx, model, prefix, cand, out, tok_logp=None):
+    import torch
+    B, n, L = cand.shape
+    _check(load_library().specs_score_blocks_static(ctx, model, prefix, _ptr(cand, torch.int32), n, L,
+                                                    _ptr(out, torch.float32), _ptr(tok_logp, torch.float32, True)),
+           "specs_score_blocks_static")
 
 
 def specs_generate_blocks(ctx, model, prefix, u, cand, logp, tok_logp=None, vocab_limit=0):

@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -12,6 +13,26 @@
     hipError_t e_ = (expr);              \
     if (e_ != hipSuccess) return SPECS_EHIP; \
   } while (0)
+
+// Scratch of specs_score_blocks_static: callers that may not allocate (code under graph capture, tight serving
+// loops) get the pass's working buffers from this array instead of a workspace. Every GPU the library runs on
+// holds its own copy at its own address; in host code the name is only a handle for hipGetSymbolAddress, so the
+// address is looked up once per device (specs_ctx_create, with that device current) and kept in
+// g_static_scratch, which is what kernels and carve() are given.
+static __device__ __align__(256) unsigned char scratch[SPECS_STATIC_SCRATCH_BYTES];
+enum { kMaxDevices = 64 };
+static char* g_static_scratch[kMaxDevices];
+static std::mutex g_static_scratch_mutex;
+
+static int resolve_static_scratch(int device) {
+  if (device < 0 || device >= kMaxDevices) return SPECS_OK;      // such a context has no static scratch
+  std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+  if (g_static_scratch[device]) return SPECS_OK;
+  void* ptr = nullptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SPECS_EHIP;
+  g_static_scratch[device] = (char*)ptr;
+  return SPECS_OK;
+}
 
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 static inline size_t esize(int dtype) { return dtype == SPECS_BF16 ? 2 : 4; }
@@ -143,6 +164,7 @@ extern "C" size_t specs_workspace_bytes(const specs_model_desc* desc, int64_t ma
 extern "C" int specs_ctx_create(int device, void* hip_stream, void* workspace, size_t workspace_bytes, specs_ctx** out) {
   if (!out || !workspace || workspace_bytes < 256 || ((uintptr_t)workspace & 255)) return SPECS_EINVAL;
   HIP_TRY(hipSetDevice(device));
+  if (int rc = resolve_static_scratch(device)) return rc;
   specs_ctx* c = new (std::nothrow) specs_ctx();
   if (!c) return SPECS_EINVAL;
   c->device = device;
@@ -468,14 +490,17 @@ static void run_trunk(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
   }
 }
 
+// base / bytes: where the pass's buffers live (the context's workspace, or the static scratch of this device).
+// The status word is the context's in both cases.
 template <typename T>
 static int score_impl(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const int32_t* cand, int n, int L,
-                      float* out, float* tok_logp) {
+                      float* out, float* tok_logp, char* base, size_t bytes) {
   const specs_model_desc& d = m->desc;
   int64_t R = (int64_t)p->B * n * L;
   int64_t C = (int64_t)p->B * n;
-  Workspace ws = carve(ctx->workspace, d, R, C);
-  if (ws.total > ctx->workspace_bytes) return SPECS_EWORKSPACE;
+  Workspace ws = carve(base, d, R, C);
+  if (ws.total > bytes) return SPECS_EWORKSPACE;
+  ws.status = (int*)ctx->workspace;
   BatchGeom g = block_geom(p, n, L);
   int max_ctx = 0;
   for (int b = 0; b < p->B; ++b) max_ctx = p->lens[b] > max_ctx ? p->lens[b] : max_ctx;
@@ -495,15 +520,16 @@ static int score_impl(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
              launch_prm_head<T>(ws.x, m->w.g_final, (const T*)m->w.head, out, g, d.d_model, d.rms_eps, s));
   }
   HIP_TRY(hipGetLastError());
-  ctx->last_model = m;
-  ctx->last_prefix = p;
+  bool in_workspace = base == ctx->workspace;        // only then can specs_commit_block find the block's keys/values
+  ctx->last_model = in_workspace ? m : nullptr;
+  ctx->last_prefix = in_workspace ? p : nullptr;
   ctx->last_n = n;
   ctx->last_L = L;
   return SPECS_OK;
 }
 
-extern "C" int specs_score_blocks(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const int32_t* cand,
-                                  int32_t n, int32_t L, float* out, float* tok_logp) {
+static int score_args_ok(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const int32_t* cand, int32_t n,
+                         int32_t L, float* out, float* tok_logp) {
   if (!ctx || !m || !p || !cand || !out) return SPECS_EINVAL;
   if (p->model != m) return SPECS_EINVAL;
   if (n <= 0 || L <= 0) return SPECS_EINVAL;
@@ -511,9 +537,28 @@ extern "C" int specs_score_blocks(specs_ctx* ctx, const specs_model* m, const sp
   if ((int64_t)p->B * n * L > (int64_t)1 << 30) return SPECS_EINVAL;
   for (int b = 0; b < p->B; ++b)
     if (p->lens[b] < 1) return SPECS_EINVAL;       // the first block token is scored from the last prefix position
+  return SPECS_OK;
+}
+
+extern "C" int specs_score_blocks(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const int32_t* cand,
+                                  int32_t n, int32_t L, float* out, float* tok_logp) {
+  if (int rc = score_args_ok(ctx, m, p, cand, n, L, out, tok_logp)) return rc;
   HIP_TRY(hipSetDevice(ctx->device));
-  return m->desc.dtype == SPECS_BF16 ? score_impl<bf16_t>(ctx, m, p, cand, n, L, out, tok_logp)
-                                     : score_impl<float>(ctx, m, p, cand, n, L, out, tok_logp);
+  return m->desc.dtype == SPECS_BF16
+             ? score_impl<bf16_t>(ctx, m, p, cand, n, L, out, tok_logp, ctx->workspace, ctx->workspace_bytes)
+             : score_impl<float>(ctx, m, p, cand, n, L, out, tok_logp, ctx->workspace, ctx->workspace_bytes);
+}
+
+extern "C" int specs_score_blocks_static(specs_ctx* ctx, const specs_model* m, const specs_prefix* p,
+                                         const int32_t* cand, int32_t n, int32_t L, float* out, float* tok_logp) {
+  if (int rc = score_args_ok(ctx, m, p, cand, n, L, out, tok_logp)) return rc;
+  if (ctx->device < 0 || ctx->device >= kMaxDevices || !g_static_scratch[ctx->device]) return SPECS_EINVAL;
+  if (ctx->prof.on) return SPECS_EINVAL;             // per-kernel timing creates events: not in this entry point
+  HIP_TRY(hipSetDevice(ctx->device));
+  char* base = g_static_scratch[ctx->device];        // the device address, never the array's name
+  return m->desc.dtype == SPECS_BF16
+             ? score_impl<bf16_t>(ctx, m, p, cand, n, L, out, tok_logp, base, SPECS_STATIC_SCRATCH_BYTES)
+             : score_impl<float>(ctx, m, p, cand, n, L, out, tok_logp, base, SPECS_STATIC_SCRATCH_BYTES);
 }
 
 // Alg. 1, Step I: n blocks of L tokens per beam, one position at a time. Step t: next-token logits from the

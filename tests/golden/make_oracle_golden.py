@@ -9,7 +9,14 @@ arithmetic float64) and stores how far that moves the outputs: the sensitivity o
 bf16 rounding of matrix operands, i.e. the floor under which no two bf16 evaluations can be expected to
 agree. The GPU parity test scales its tolerance by it.
 
-usage: python tests/golden/make_oracle_golden.py c3_1p5b [--beams 0,1] [--noise]
+--layers K evaluates every role with its first K layers only, at full widths, and writes
+oracle_<config>_L<K>.json: the depth series that separates an error that grows with depth (rounding
+decisions that decorrelate) from one that is there at depth 1 (a mistake).
+
+--append adds the given beams to the beams a stored file already holds (configuration 5: each beam
+costs up to an hour), keeping what is stored.
+
+usage: python tests/golden/make_oracle_golden.py c3_1p5b [--beams 0,1] [--noise] [--layers 2] [--append]
 """
 import dataclasses
 import argparse
@@ -27,24 +34,68 @@ import workload as W  # noqa: E402
 from workload.configs import HostWeights  # noqa: E402
 
 
+def append_beams(args, wl, beams, old, path):
+    """Scores `beams` and appends them, beam by beam, to the lists of a stored file (written after every beam and role)."""
+    pt_all, cand_all = wl.prefix_tokens(), wl.candidates()
+    partial = path[:-5] + ".partial.json"
+    done = json.load(open(partial)) if os.path.exists(partial) else {}
+    for b in beams:
+        for role in args.roles.split(","):
+            key = f"{b}/{role}"
+            if key in done:
+                continue
+            desc = wl.models()[role]
+            t0 = time.time()
+            hw = HostWeights(desc, wl.seed)
+            res = oracle.score_cached(desc, hw, oracle.prefill(desc, hw, [pt_all[b]]), cand_all[[b]])
+            done[key] = np.asarray(res).tolist() if desc.head == "prm" else [res[0].tolist(), res[1].tolist()]
+            print("beam", b, role, round(time.time() - t0, 1), "s", flush=True)
+            json.dump(done, open(partial, "w"))
+    for b in beams:
+        old["beams"].append(b)
+        for role in args.roles.split(","):
+            r = done[f"{b}/{role}"]
+            if wl.models()[role].head == "prm":
+                old[role] += r
+            else:
+                old[role] += r[0]
+                old["tok_" + role] += r[1]
+    old["note_appended"] = ("noise_* and seconds_* fields were measured on the first two beams stored; "
+                            "later beams were appended without a sensitivity run")
+    json.dump(old, open(path, "w"))
+    os.remove(partial)
+    print("appended", beams, "to", path)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("config")
     ap.add_argument("--beams", default=None, help="comma-separated beam indices (default: all)")
     ap.add_argument("--roles", default="target,draft,prm")
     ap.add_argument("--noise", action="store_true")
+    ap.add_argument("--layers", type=int, default=0)
+    ap.add_argument("--append", action="store_true")
     args = ap.parse_args()
     wl = W.get_config(args.config)
+    tag = args.config
+    if args.layers:
+        wl = W.configs.scaled(wl, **{r: dataclasses.replace(m, n_layers=min(args.layers, m.n_layers))
+                                     for r, m in wl.models().items()})
+        tag = f"{args.config}_L{args.layers}"
     beams = list(range(wl.B)) if args.beams is None else [int(b) for b in args.beams.split(",")]
     pt_all, cand_all = wl.prefix_tokens(), wl.candidates()
     pt, cand = [pt_all[b] for b in beams], cand_all[beams]
     out = {"config": args.config, "beams": beams, "seed": wl.seed,
            "note": "float64 oracle, cached mode (proved equal to full recompute in tests/test_oracle_scoring.py)"}
-    path = os.path.join(ROOT, "tests", "golden", f"oracle_{args.config}.json")
-    if os.path.exists(path):
-        old = json.load(open(path))
-        if old.get("beams") == beams:
-            out.update({k: v for k, v in old.items() if k not in out})
+    if args.layers:
+        out["layers"] = args.layers
+    path = os.path.join(ROOT, "tests", "golden", f"oracle_{tag}.json")
+    old = json.load(open(path)) if os.path.exists(path) else None
+    if args.append:
+        assert old is not None and not args.noise and not set(beams) & set(old["beams"])
+        return append_beams(args, wl, beams, old, path)
+    if old is not None and old.get("beams") == beams:
+        out.update({k: v for k, v in old.items() if k not in out})
     for role in args.roles.split(","):
         desc = wl.models()[role]
         t0 = time.time()

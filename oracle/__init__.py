@@ -5,7 +5,7 @@ check and the benchmark's cpu_baseline leg may import it; the product path never
 It imports nothing from the HIP package and shares no code with it.
 """
 from .rounding import round_bf16, operand
-from .transformer import (linear, gate_up, token_logprob, silu, log_softmax, rms_norm, rope, swiglu_ffn, attention, forward_sequences,
+from .transformer import (linear, token_logprob, silu, log_softmax, rms_norm, rope, swiglu_ffn, attention, forward_sequences,
                           block_logprobs_full, reward_full, prefill, score_cached, PrefixCache)
 from .subsample import scores, selection_probs, subsample, subsample_batch
 from . import smc

@@ -57,11 +57,6 @@ def linear(a, w):
     return np.asarray(a, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T
 
 
-def gate_up(a, wg, wu, dtype):
-    """First half of the SwiGLU feed-forward: silu(a Wg^T) * (a Wu^T), rounded as the operand of the down projection."""
-    return operand(silu(linear(a, wg)) * linear(a, wu), dtype)
-
-
 def token_logprob(a, w_head, targets):
     """log softmax(a W^T)[target] per row: the chain-rule term of one token."""
     lp = log_softmax(linear(a, w_head))

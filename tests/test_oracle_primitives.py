@@ -119,3 +119,50 @@ def test_reward_head_is_a_logistic_of_the_normalised_state():
     r = T._reward(D, W(), h)
     assert np.allclose(r, [1 / (1 + np.exp(1.5)), 0.5])
     assert np.all((r > 0) & (r < 1))
+
+
+def test_linear_is_the_row_by_row_dot_product_with_stored_rows():
+    """y = a W^T for W stored [out, in]: pinned by hand-set operands (a transposed or mis-indexed operand
+    gives a different matrix), by explicit dot products, and by the library routine in a different formulation."""
+    a = np.array([[1.0, 2.0, 3.0], [0.0, -1.0, 0.5]])
+    w = np.array([[1.0, 0.0, 0.0], [0.0, 1.0, 1.0], [2.0, 2.0, 2.0], [-1.0, 0.5, 0.0]])     # [out=4, in=3]
+    want = np.array([[1.0, 5.0, 12.0, 0.0], [0.0, -0.5, -1.0, -0.5]])
+    assert np.array_equal(oracle.linear(a, w), want)
+    A, Wm = RNG.standard_normal((9, 33)), RNG.standard_normal((17, 33))
+    y = oracle.linear(A, Wm)
+    assert y.shape == (9, 17)
+    for m in (0, 4, 8):
+        for n in (0, 7, 16):
+            assert abs(y[m, n] - sum(A[m, k] * Wm[n, k] for k in range(33))) < 1e-12
+    assert np.allclose(y, F.linear(torch.from_numpy(A), torch.from_numpy(Wm)).numpy(), atol=1e-12)
+    # float32 inputs are promoted, not multiplied in float32
+    a32, w32 = A.astype(np.float32), Wm.astype(np.float32)
+    assert oracle.linear(a32, w32).dtype == np.float64
+    assert np.allclose(oracle.linear(a32, w32), a32.astype(np.float64) @ w32.astype(np.float64).T, atol=1e-14)
+
+
+def test_token_logprob_is_minus_cross_entropy_and_picks_the_right_column():
+    """log softmax(a W^T)[target] per row: equals minus the library's per-row cross entropy, sums to one over
+    all targets, and on a hand-set case with logits (0, ln 2, ln 3) gives ln(1/6), ln(2/6), ln(3/6)."""
+    Wm = np.eye(3)
+    a = np.array([[0.0, np.log(2.0), np.log(3.0)]] * 3)
+    got = oracle.token_logprob(a, Wm, [0, 1, 2])
+    assert np.allclose(got, np.log([1 / 6, 2 / 6, 3 / 6]), atol=1e-15)
+    A, Wh = RNG.standard_normal((11, 24)), RNG.standard_normal((50, 24))
+    tg = RNG.integers(0, 50, 11)
+    z = torch.from_numpy(A) @ torch.from_numpy(Wh).T
+    want = -F.cross_entropy(z, torch.from_numpy(tg), reduction="none").numpy()
+    assert np.allclose(oracle.token_logprob(A, Wh, tg), want, atol=1e-12)
+    # each row is a distribution over targets, and rows do not mix: row r with every target
+    for r in (0, 10):
+        allp = oracle.token_logprob(np.repeat(A[r:r + 1], 50, axis=0), Wh, np.arange(50))
+        assert abs(np.exp(allp).sum() - 1.0) < 1e-12
+        assert abs(allp[tg[r]] - want[r]) < 1e-12
+    # the model's own vocabulary-head path (final norm with unit gains on unit-mean-square rows = identity)
+    class _W:
+        def gains(self): return {"final": np.ones(24)}
+        def head(self): return Wh
+    class _D:
+        rms_eps, dtype = 0.0, "f32"
+    unit = np.sign(A)
+    assert np.allclose(T._token_logprobs(_D, _W(), unit, tg), oracle.token_logprob(unit, Wh, tg), atol=1e-12)

@@ -5,10 +5,35 @@ in wider precision ("bf16 weights and activations with fp32 accumulate" in the w
 statement; the paper itself fixes no precision). The oracle keeps all arithmetic in float64
 and applies one round-to-nearest-even to bf16 at exactly the points where an operand of a
 matrix product is formed: the normalised input of a projection, Q/K/V after the rotary
-embedding, the un-normalised softmax weights before they multiply V, the attention output,
+embedding, the un-normalised softmax weights (relative to a power-of-two reference) before they multiply V, the attention output,
 and the SwiGLU product. For the "f32" configuration nothing is rounded.
 """
+import contextlib
 import numpy as np
+
+# Relative jitter applied to a value just before it is rounded to bf16 (None: exact float64 values are rounded).
+_JITTER = None
+
+
+@contextlib.contextmanager
+def float_accumulation_jitter(amplitude=2.0e-7, seed=0):
+    """Within this context every operand is multiplied by (1 + amplitude * N(0,1)) before it is rounded to bf16.
+
+    A tolerance-derivation tool, not part of the definition. An implementation that honours the rounding points
+    but accumulates its matrix products in float carries a relative error of a few 1e-7 (the accumulated float
+    rounding of a few thousand terms) into every rounding decision. A value that sits within that distance of a
+    bf16 rounding boundary then rounds the other way, which moves the operand by a whole bf16 unit; the moved
+    operands perturb the next rounding stage by far more than 1e-7, and after two or three stages the two
+    evaluations differ by about as much as two independent bf16 roundings would. Evaluating the oracle with and
+    without this jitter measures how close ANY float-accumulating evaluation of the same rounding contract can be
+    expected to come to the float64 oracle on a given model and input."""
+    global _JITTER
+    old = _JITTER
+    _JITTER = (float(amplitude), np.random.default_rng(seed))
+    try:
+        yield
+    finally:
+        _JITTER = old
 
 
 def round_bf16(x):
@@ -25,5 +50,9 @@ def operand(x, dtype):
     if dtype == "f32":
         return np.asarray(x, dtype=np.float64)
     if dtype == "bf16":
+        if _JITTER is not None:
+            amp, rng = _JITTER
+            x = np.asarray(x, dtype=np.float64)
+            x = x * (1.0 + amp * rng.standard_normal(x.shape))
         return round_bf16(x)
     raise ValueError(dtype)

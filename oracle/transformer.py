@@ -71,23 +71,29 @@ def swiglu_ffn(a, wg, wu, wd, dtype):
 def attention(q, k, v, mask, dtype):
     """q [T, Hq, hd]; k, v [S, Hkv, hd]; mask [T, S] (True = may attend) -> [T, Hq*hd].
 
-    Query head h reads key/value head h // (Hq/Hkv). Softmax weights are rounded as a matrix
-    operand in their un-normalised form exp(s - max s); the normaliser sums the unrounded ones.
+    Query head h reads key/value head h // (Hq/Hkv). out = softmax(q k^T / sqrt(hd)) v. The softmax weights
+    are rounded as a matrix operand in un-normalised form relative to a power-of-two reference:
+    w = 2^(s' - ceil(max s')) with s' = s log2(e), i.e. the row's weights divided by the smallest power of two
+    that is not below the largest of them. Rounding to bf16 commutes with scaling by a power of two, so ANY
+    power-of-two reference yields the same rounded operand up to that scale: an evaluation that walks the keys in
+    tiles and only knows a running maximum rounds the same values as this one, which knows the global maximum.
+    The normaliser sums the unrounded weights.
     """
     T, Hq, hd = q.shape
     S, Hkv, _ = k.shape
     g = Hq // Hkv
     scale = 1.0 / np.sqrt(float(hd))
+    log2e = 1.0 / np.log(2.0)
     out = np.empty((T, Hq, hd), dtype=np.float64)
     step = max(1, (1 << 25) // max(S, 1))
     for h in range(Hq):
         kh, vh = k[:, h // g, :], v[:, h // g, :]
         for t0 in range(0, T, step):
             t1 = min(T, t0 + step)
-            s = (q[t0:t1, h, :] @ kh.T) * scale
-            s = np.where(mask[t0:t1], s, -np.inf)
-            p = np.exp(s - s.max(axis=-1, keepdims=True))
-            out[t0:t1, h, :] = (operand(p, dtype) @ vh) / p.sum(axis=-1, keepdims=True)
+            s2 = (q[t0:t1, h, :] @ kh.T) * (scale * log2e)
+            s2 = np.where(mask[t0:t1], s2, -np.inf)
+            w = np.exp2(s2 - np.ceil(s2.max(axis=-1, keepdims=True)))
+            out[t0:t1, h, :] = (operand(w, dtype) @ vh) / w.sum(axis=-1, keepdims=True)
     return out.reshape(T, Hq * hd)
 
 

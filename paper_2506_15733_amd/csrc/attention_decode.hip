@@ -51,7 +51,8 @@ __global__ void __launch_bounds__(64) attention_decode_merge_kernel(
     mx = fmaxf(mx, dot);
   }
   for (int s = lane; s < n_splits; s += 64) mx = fmaxf(mx, part_m[prow0 + (size_t)s * 128]);
-  mx = wave_max(mx);                            // finite: key t itself is always visible
+  mx = ceilf(wave_max(mx));                     // finite (key t itself is always visible); an integer, so that
+                                                // the bf16 rounding of the weights does not depend on the reference
   float l = 0.f;
   for (int jk = lane; jk <= t; jk += 64) {
     float p = __builtin_amdgcn_exp2f(sc[jk] - mx);
@@ -160,7 +161,8 @@ __global__ void __launch_bounds__(64) attention_decode_merge_fast_kernel(
     dots[kk] = lane + 64 * kk <= t ? dot * scale_log2e : -INFINITY;
     mx = fmaxf(mx, dots[kk]);
   }
-  mx = wave_max(mx);                            // finite: key t itself is always visible
+  mx = ceilf(wave_max(mx));                     // finite (key t itself is always visible); an integer, so that
+                                                // the bf16 rounding of the weights does not depend on the reference
   float l = 0.f;
 #pragma unroll
   for (int kk = 0; kk < 2; ++kk) {

@@ -277,14 +277,17 @@ __global__ void __launch_bounds__(256, QT == 1 ? 2 : 1) attention_mfma_kernel(At
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[u][hf][r]);
       mx = half_wave_max(mx);
       // Reference exponent of the row in the log2 domain (scores are scaled by scale*log2(e) > 0 inside the
-      // exponent's FMA). It follows the row maximum lazily: the accumulators are rescaled only when the maximum has
-      // grown by more than 2^RESCALE_LOG2 past the reference, so weights reach at most that factor (exact in
-      // float; O/l at the end does not depend on the reference) and the 64 multiplications per lane become rare.
+      // exponent's FMA). It is always an INTEGER: the weights that multiply V are rounded to bf16, and that rounding
+      // commutes with a power-of-two scale, so the rounded operand is the same whichever integer reference a tile
+      // happens to see (a streaming evaluation and one that knows the global maximum round the same values). It
+      // follows the row maximum lazily: the accumulators are rescaled only when the maximum has grown by more than
+      // 2^RESCALE_LOG2 past the reference, so weights reach at most that factor (exact in float; O/l at the end
+      // does not depend on the reference) and the 64 multiplications per lane become rare.
       constexpr float RESCALE_LOG2 = 8.f;
       const float m_tile = mx * a.scale_log2e;
       const bool move = m_tile > m_run[u] + RESCALE_LOG2;   // also the first visible key: -inf + 8 = -inf
       if (__any(move)) {
-        const float m_new = move ? m_tile : m_run[u];
+        const float m_new = move ? ceilf(m_tile) : m_run[u];
         const float alpha = move ? __builtin_amdgcn_exp2f(m_run[u] - m_new) : 1.f;   // exp2(-inf) = 0: nothing yet
         l_run[u] *= alpha;
 #pragma unroll

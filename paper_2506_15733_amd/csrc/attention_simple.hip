@@ -1,7 +1,9 @@
 // Straightforward shared-prefix attention: one wavefront per (row, query head). Serves the float
 // configuration, head sizes the MFMA kernel does not take, and launches that cover one in-block position of every
 // candidate (row m = candidate m / L at position t0 + m % L; its block keys are rows cand*Lk .. of kb). Three passes over the keys:
-// scores into LDS (+ max), un-normalised weights exp(s - max) (+ sum), weighted sum of V.
+// scores into LDS (+ max), un-normalised weights 2^(s' - ceil(max s')) in the log2 domain (+ sum; the integer
+// reference makes the bf16 rounding of the weights independent of which power of two they are scaled by), weighted
+// sum of V.
 #include "common.h"
 
 template <typename T>
@@ -33,14 +35,14 @@ __global__ void __launch_bounds__(64) attention_simple_kernel(const T* __restric
     }
     float dot = 0.f;
     for (int c = 0; c < hd; ++c) dot = fmaf(qs[c], to_f32<T>(kr[c]), dot);
-    dot *= scale;
+    dot *= scale;                                // scale = log2(e) / sqrt(hd): scores in the log2 domain
     sc[j] = dot;
     mx = fmaxf(mx, dot);
   }
-  mx = wave_max(mx);
+  mx = ceilf(wave_max(mx));
   float sm = 0.f;
   for (int j = lane; j < nkeys; j += 64) {
-    float p = expf(sc[j] - mx);
+    float p = exp2f(sc[j] - mx);
     sm += p;
     sc[j] = to_f32<T>(from_f32<T>(p));          // the weight that multiplies V is an operand: rounded to T
   }
@@ -70,7 +72,7 @@ template <typename T>
 void launch_attention_simple(const T* q, const T* kb, const T* vbT, const T* poolK, const T* poolV, T* out,
                              const BatchGeom& g, const ModelDims& md, int Lp, int max_ctx, hipStream_t s) {
   size_t lds = (size_t)(max_ctx + g.Lk + md.hd) * sizeof(float);
-  float scale = 1.0f / sqrtf((float)md.hd);
+  float scale = 1.4426950408889634f / sqrtf((float)md.hd);
   (void)hipFuncSetAttribute((const void*)attention_simple_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   attention_simple_kernel<T><<<dim3(g.M, md.Hq), 64, lds, s>>>(q, kb, vbT, poolK, poolV, out, g, md.Hq, md.Hkv, md.hd,
                                                                Lp, scale);

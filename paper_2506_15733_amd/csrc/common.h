@@ -101,6 +101,12 @@ bool launch_attention_mfma(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT,
                            const bf16_t* poolV, bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp,
                            int max_ctx, float* part, size_t part_floats, hipStream_t s);
 
+// The same launches with the two-phase schedule (attention_pingpong.hip): 256 stacked rows of all candidates of a
+// (beam, kv head) per workgroup. False if the shape is not taken.
+bool launch_attention_pingpong(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT, const bf16_t* poolK,
+                               const bf16_t* poolV, bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp,
+                               int max_ctx, float* part, size_t part_floats, hipStream_t s);
+
 // One in-block position per candidate (g.L == 1, position g.t0): prefix keys by the MFMA kernel in split mode,
 // merged with the candidate's own block keys. part: scratch of part_floats floats. False if the shape is not taken.
 bool launch_attention_decode(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT, const bf16_t* poolK,
@@ -125,6 +131,8 @@ enum { MFMA_STORE = 0, MFMA_RESIDUAL = 1, MFMA_SWIGLU = 2, MFMA_LMHEAD = 3 };
 bool launch_gemm_mfma(int epi, const bf16_t* A, const bf16_t* W, int M, int N, int K, float* C, bf16_t* act,
                       const int32_t* tok, float* part_max, float* part_sum, float* zt, int ksplit, int bm,
                       hipStream_t s);
+bool launch_gemm_mfma_qkv_rope(const bf16_t* A, const bf16_t* W, const float* cs, bf16_t* q, bf16_t* kblk, bf16_t* vT,
+                               const BatchGeom& g, const ModelDims& md, int Lp, hipStream_t s);
 // tile height and number of K slices for a product whose consumer sums up to max_split partial products
 void mfma_gemm_plan(int M, int N, int K, int max_split, int* bm_out, int* split_out);
 // x[M,d] (+)= sum of `parts` partial products P[parts][M,d]; init != 0 overwrites x instead of adding to it.

@@ -26,7 +26,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
-enum MfmaEpilogue { ME_STORE = 0, ME_RESIDUAL = 1, ME_SWIGLU = 2, ME_LMHEAD = 3 };
+enum MfmaEpilogue { ME_STORE = 0, ME_RESIDUAL = 1, ME_SWIGLU = 2, ME_LMHEAD = 3, ME_QKV_ROPE = 4 };
 
 struct GemmArgs {
   const bf16_t* A;
@@ -41,11 +41,21 @@ struct GemmArgs {
   float* part_sum;
   float* zt;             // ME_LMHEAD: [M]
   int ksplit;            // ME_STORE only: gridDim.y slices of K, slice s writes its partial product to C + s*M*N
+  // ME_QKV_ROPE: the product is the QKV projection [M, (Hq + 2 Hkv) * hd]; the epilogue rotates the q and k heads
+  // (pairs (i, i + hd/2), angles from the table cs[M][hd] = cos | sin) and writes bf16 q [M][Hq][hd], block keys
+  // kblk[cand*Lk + t][Hkv][hd] and block values transposed per candidate vT[cand][Hkv][hd][Lp], where row m is
+  // in-block position t = t0 + m % Lrows of candidate m / Lrows.
+  const float* cs;
+  bf16_t* q;
+  bf16_t* kblk;
+  bf16_t* vT;
+  int Hq, Hkv, hd, Lrows, t0, Lk, Lp;
 };
 
 // One direct-to-LDS load instruction: the workgroup's NW wavefronts write NW consecutive 1 KiB spans
 // (8 rows of 128 bytes each) of an operand tile.
-template <int NW>
+// SWAP56: LDS row r holds tile row r with bits 5 and 6 exchanged (see the ME_QKV_ROPE epilogue).
+template <int NW, bool SWAP56 = false>
 __device__ __forceinline__ void load_span_async(const bf16_t* __restrict__ G, int row0, int rows_total, int K, int k0,
                                                 char* lds_tile, int p, int wave) {
   const int lane = threadIdx.x & 63;
@@ -53,7 +63,7 @@ __device__ __forceinline__ void load_span_async(const bf16_t* __restrict__ G, in
   int q = span * 64 + lane;
   int row = q >> 3, slot = q & 7;
   int chunk = slot ^ ((row >> 1) & 7);
-  int grow = row0 + row;
+  int grow = row0 + (SWAP56 ? ((row & ~0x60) | ((row & 0x20) << 1) | ((row & 0x40) >> 1)) : row);
   grow = grow < rows_total ? grow : rows_total - 1;
   const bf16_t* src = G + (size_t)grow * K + k0 + chunk * 8;
   __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(lds_tile + span * 1024), 16, 0, 0);
@@ -74,9 +84,15 @@ __device__ __forceinline__ float half_wave_sum(float v) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int BM, int EPI, int NWN>
+// HD128 (ME_QKV_ROPE only): head_dim 128 instead of 64.
+template <int BM, int EPI, int NWN, bool HD128 = false>
 __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   constexpr int BN = 256;
+  // Rotary pairs are columns (i, i + hd/2) of a head. With head_dim 64 a wavefront's 64 columns are one head and
+  // its two accumulator columns the two halves. With head_dim 128 a head spans two wavefronts, so the W tile is
+  // loaded with rows 32..63 and 64..95 of every 128 exchanged: wavefront (head, wq) then holds columns
+  // wq*32 .. +31 of the first half in accumulator column 0 and the same columns of the second half in column 1.
+  constexpr bool SWAP = EPI == ME_QKV_ROPE && HD128;
   constexpr int NW = 2 * NWN;                         // wavefronts: 2 along M x NWN along N
   constexpr int WM = BM / 2, TM = WM / 32, WN = BN / NWN, TN = WN / 32;
   // All epilogues multiply W-fragment x A-fragment, i.e. the transposed 32x32 product: a lane then holds runs of
@@ -137,7 +153,7 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   auto issue_w = [&](int t) {                           // prologue only: t < 5 is its own phase
     const int src = t < KT ? t : KT - 1;
 #pragma unroll
-    for (int i = 0; i < LB; ++i) load_span_async<NW>(a.W, n0, a.N, a.K, (kt0 + src) * 64, wslot(t), i, wave);
+    for (int i = 0; i < LB; ++i) load_span_async<NW, SWAP>(a.W, n0, a.N, a.K, (kt0 + src) * 64, wslot(t), i, wave);
   };
   auto issue_a = [&](int t) {
     const int src = t < KT ? t : KT - 1;
@@ -156,7 +172,7 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
     for (int j = 0; j < NLD; ++j) {
       if (j * 4 / NLD != SH) continue;
       if (j < LA) load_span_async<NW>(a.A, m0, a.M, a.K, (kt0 + sa) * 64, aslot(pa), j, wave);
-      else load_span_async<NW>(a.W, n0, a.N, a.K, (kt0 + sw) * 64, wslot(pw), j - LA, wave);
+      else load_span_async<NW, SWAP>(a.W, n0, a.N, a.K, (kt0 + sw) * 64, wslot(pw), j - LA, wave);
     }
   };
 #define SGB __builtin_amdgcn_sched_group_barrier
@@ -266,6 +282,57 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
     };
     if (inside) emit(std::false_type{});
     else emit(std::true_type{});
+  } else if (EPI == ME_QKV_ROPE) {
+    static_assert(EPI != ME_QKV_ROPE || (TN == 2 && NWN == 4), "one rotary half per accumulator column");
+    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+    constexpr int HDIM = HD128 ? 128 : 64, HALF = HDIM / 2;
+    const int head = HD128 ? (n0 >> 7) + (wn >> 1) : (n0 >> 6) + wn;
+    const int i_base = (HD128 ? (wn & 1) * 32 : 0) + 4 * lhalf;          // + 8 g + e: index of the pair inside the head
+    if (head < a.Hq + 2 * a.Hkv) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = m0 + wm * WM + i * 32 + lrow;
+        if (row >= a.M) continue;
+        const int cand = row / a.Lrows, t = a.t0 + (row - cand * a.Lrows);
+        if (head < a.Hq + a.Hkv) {
+          const float* cs = a.cs + (size_t)row * HDIM;
+          bf16_t* dst = head < a.Hq ? a.q + ((size_t)row * a.Hq + head) * HDIM
+                                    : a.kblk + (((size_t)cand * a.Lk + t) * a.Hkv + (head - a.Hq)) * HDIM;
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int i0 = i_base + 8 * g;
+            const float4 cn = *(const float4*)(cs + i0), sn = *(const float4*)(cs + HALF + i0);
+            const float c4[4] = {cn.x, cn.y, cn.z, cn.w}, s4[4] = {sn.x, sn.y, sn.z, sn.w};
+            bf16x4 y1, y2;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float x1 = acc[i][0][4 * g + e], x2 = acc[i][1][4 * g + e];
+              y1[e] = (__bf16)(x1 * c4[e] - x2 * s4[e]);
+              y2[e] = (__bf16)(x2 * c4[e] + x1 * s4[e]);
+            }
+            *(bf16x4*)(dst + i0) = y1;
+            *(bf16x4*)(dst + HALF + i0) = y2;
+          }
+        } else {
+          // values: not rotated, stored transposed; the 32 lanes of a half-wave write 32 consecutive positions
+          bf16_t* dst = a.vT + (((size_t)cand * a.Hkv + (head - a.Hq - a.Hkv)) * HDIM) * a.Lp + t;
+          const bool pad = t == a.Lk - 1 && a.Lp > a.Lk;
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int d = i_base + 8 * g + e;
+              dst[(size_t)d * a.Lp] = (__bf16)acc[i][0][4 * g + e];
+              dst[(size_t)(HALF + d) * a.Lp] = (__bf16)acc[i][1][4 * g + e];
+              if (pad)
+                for (int tt = 1; tt < a.Lp - t; ++tt) {
+                  dst[(size_t)d * a.Lp + tt] = (__bf16)0.f;
+                  dst[(size_t)(HALF + d) * a.Lp + tt] = (__bf16)0.f;
+                }
+            }
+        }
+      }
+    }
   } else {  // ME_LMHEAD
     __syncthreads();                                   // every wavefront is done with the operand tiles
     float* red_max = (float*)smem;                     // [BM][NWN]
@@ -327,18 +394,18 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   }
 }
 
-template <int BM, int EPI, int NWN>
+template <int BM, int EPI, int NWN, bool HD128 = false>
 static void launch_variant(const GemmArgs& a, hipStream_t s) {
   constexpr int smem = 5 * 256 * 128;
   static bool configured = false;
   if (!configured) {
-    (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, EPI, NWN>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              smem);
+    (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, EPI, NWN, HD128>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     configured = true;
   }
   int per_xcd = (a.n_tiles + 7) / 8;                 // N-tiles owned by one XCD
   int blocks = a.m_blocks * ((per_xcd + 3) / 4);     // 8 x 4 blocks per XCD
-  gemm_mfma_kernel<BM, EPI, NWN><<<dim3(blocks * 32 * 8, a.ksplit), 128 * NWN, smem, s>>>(a);
+  gemm_mfma_kernel<BM, EPI, NWN, HD128><<<dim3(blocks * 32 * 8, a.ksplit), 128 * NWN, smem, s>>>(a);
 }
 
 int mfma_lmhead_tiles(int V) { return (V + 255) / 256; }
@@ -362,6 +429,28 @@ void mfma_gemm_plan(int M, int N, int K, int max_split, int* bm_out, int* split_
   }
 }
 
+// QKV projection with the rotary embedding, the bf16 conversion and the per-candidate transposition of the values
+// in the epilogue: no float [M, (Hq+2Hkv)*hd] round trip through memory and no separate kernel. Row m is in-block
+// position g.t0 + m % g.L of candidate m / g.L. Returns false when the shape is not taken (head_dim other than
+// 64/128, K % 64 != 0, misaligned buffers); the caller then runs the projection and the rotary kernel separately.
+bool launch_gemm_mfma_qkv_rope(const bf16_t* A, const bf16_t* W, const float* cs, bf16_t* q, bf16_t* kblk, bf16_t* vT,
+                               const BatchGeom& g, const ModelDims& md, int Lp, hipStream_t s) {
+  const int M = g.M, N = (md.Hq + 2 * md.Hkv) * md.hd, K = md.d;
+  if (K % 64 != 0 || M <= 0 || (md.hd != 64 && md.hd != 128)) return false;
+  if (((uintptr_t)cs & 15) || ((uintptr_t)q & 7) || ((uintptr_t)kblk & 7)) return false;
+  GemmArgs a = {};
+  a.A = A; a.W = W; a.M = M; a.N = N; a.K = K; a.ksplit = 1;
+  a.cs = cs; a.q = q; a.kblk = kblk; a.vT = vT;
+  a.Hq = md.Hq; a.Hkv = md.Hkv; a.hd = md.hd; a.Lrows = g.L; a.t0 = g.t0; a.Lk = g.Lk; a.Lp = Lp;
+  a.n_tiles = (N + 255) / 256;
+  bool small = ((M + 255) / 256) * a.n_tiles <= 128 || M <= 128;
+  a.m_tiles = small ? (M + 127) / 128 : (M + 255) / 256;
+  a.m_blocks = (a.m_tiles + 7) / 8;
+  if (md.hd == 128) { if (small) launch_variant<128, ME_QKV_ROPE, 4, true>(a, s); else launch_variant<256, ME_QKV_ROPE, 4, true>(a, s); }
+  else { if (small) launch_variant<128, ME_QKV_ROPE, 4, false>(a, s); else launch_variant<256, ME_QKV_ROPE, 4, false>(a, s); }
+  return true;
+}
+
 // Returns false when the shape is not one this kernel takes (the caller then uses the SIMT kernel).
 // ksplit > 1 (ME_STORE only): C is [ksplit][M][N] and receives the partial products of the K slices.
 // bm: tile height 128 or 256, 0 = chosen here.
@@ -372,7 +461,7 @@ bool launch_gemm_mfma(int epi, const bf16_t* A, const bf16_t* W, int M, int N, i
   if (epi == ME_SWIGLU && (N % 64 != 0 || ((uintptr_t)act & 7))) return false;
   if (ksplit < 1 || (ksplit > 1 && (epi != ME_STORE || ksplit > K / 64))) return false;
   if (bm != 0 && bm != 128 && bm != 256) return false;
-  GemmArgs a;
+  GemmArgs a = {};
   a.A = A; a.W = W; a.M = M; a.N = N; a.K = K; a.C = C; a.act = act; a.tok = tok;
   a.part_max = part_max; a.part_sum = part_sum; a.zt = zt; a.ksplit = ksplit;
   a.n_tiles = (N + 255) / 256;

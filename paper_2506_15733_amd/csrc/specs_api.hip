@@ -366,6 +366,17 @@ int gemm_store_split<bf16_t>(const bf16_t* A, const bf16_t* W, float* C, int max
   return 1;
 }
 
+template <typename T>
+static bool qkv_rope_fused(const T*, const T*, const float*, T*, T*, T*, const BatchGeom&, const ModelDims&, int,
+                           hipStream_t) {
+  return false;
+}
+template <>
+bool qkv_rope_fused<bf16_t>(const bf16_t* A, const bf16_t* W, const float* cs, bf16_t* q, bf16_t* kb, bf16_t* vT,
+                            const BatchGeom& g, const ModelDims& md, int Lp, hipStream_t s) {
+  return launch_gemm_mfma_qkv_rope(A, W, cs, q, kb, vT, g, md, Lp, s);
+}
+
 // act[M,F] = silu(A Wg^T) * (A Wu^T) with Wgu interleaved by 32 rows
 template <typename T>
 static void gate_up(const T* A, const T* Wgu, float* gu, T* act, int M, int F, int K, hipStream_t s) {
@@ -431,11 +442,18 @@ static void run_trunk(specs_ctx* ctx, const specs_model* m, const specs_prefix* 
     T* pK = pool_ptr<T>(p, d, l, 0);
     T* pV = pool_ptr<T>(p, d, l, 1);
     if (!normed) PROFILED(ctx, SPECS_K_OTHER, s, launch_rmsnorm<T>(x, L.g_attn, (T*)ws.a, g.M, md.d, md.eps, s));
-    int qkv_parts = 1;                                   // ws.qkv has room for R / g.M slices of the projection
-    PROFILED(ctx, SPECS_K_QKV, s,
-             qkv_parts = gemm_store_split<T>((const T*)ws.a, (const T*)L.wqkv, ws.qkv, (int)(R / g.M < 8 ? R / g.M : 8),
-                                             g.M, qd + 2 * kvd, md.d, s));
-    PROFILED(ctx, SPECS_K_OTHER, s, launch_rope_split<T>(ws.qkv, qkv_parts, ws.cs, (T*)ws.q, kb, vb, g, Lp, md, s));
+    // whole-block bf16 launches: rotary embedding, conversion and value transposition inside the projection's epilogue
+    bool fused_rope = false;
+    if (g.M > 32)
+      PROFILED(ctx, SPECS_K_QKV, s,
+               fused_rope = qkv_rope_fused<T>((const T*)ws.a, (const T*)L.wqkv, ws.cs, (T*)ws.q, kb, vb, g, md, Lp, s));
+    if (!fused_rope) {
+      int qkv_parts = 1;                                 // ws.qkv has room for R / g.M slices of the projection
+      PROFILED(ctx, SPECS_K_QKV, s,
+               qkv_parts = gemm_store_split<T>((const T*)ws.a, (const T*)L.wqkv, ws.qkv, (int)(R / g.M < 8 ? R / g.M : 8),
+                                               g.M, qd + 2 * kvd, md.d, s));
+      PROFILED(ctx, SPECS_K_OTHER, s, launch_rope_split<T>(ws.qkv, qkv_parts, ws.cs, (T*)ws.q, kb, vb, g, Lp, md, s));
+    }
     if (last_token_only && l == d.n_layers - 1 && g.L > 1 && g.t0 == 0 && !commit_pages) {
       BatchGeom gl = g;                                  // one row per block: its last position
       gl.L = 1; gl.M = (int)C; gl.t0 = g.L - 1; gl.Lk = g.L;
@@ -786,7 +804,12 @@ void attention<bf16_t>(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT, con
                        bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp, int max_ctx, float* scratch,
                        size_t scratch_floats, hipStream_t s) {
   bool whole_blocks = g.t0 == 0 && g.Lk == g.L;
-  bool done = whole_blocks ? launch_attention_mfma(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, scratch, scratch_floats, s)
+  // Launches with at least ~160 workgroups of 256 stacked rows take the two-phase kernel (measured 3-8 % faster
+  // at the 7B shapes); smaller ones the one-phase kernel, which cuts long key lists over several workgroups.
+  const long stacked = (long)g.B * md.Hkv * (((long)g.n * g.L * (md.Hq / md.Hkv) + 255) / 256);
+  bool done = whole_blocks ? ((stacked >= 160 &&
+                               launch_attention_pingpong(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, nullptr, 0, s)) ||
+                              launch_attention_mfma(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, scratch, scratch_floats, s))
                            : (g.L == 1 && scratch &&
                               launch_attention_decode(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, scratch,
                                                       scratch_floats, s));

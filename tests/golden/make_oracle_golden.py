@@ -4,6 +4,10 @@ Calls only `oracle` (and the input generators in `workload`); nothing here touch
 The large configurations take minutes (c3) to an hour (c4) of float64 BLAS time, which is why
 their expected values are stored instead of being recomputed inside the GPU test run.
 
+With --floor it also evaluates every role under oracle.float_accumulation_jitter (a relative error of 2e-7 in every
+value that gets rounded to bf16) and stores how far that moves the outputs: what a float-accumulating evaluation of the
+same rounding contract can be expected to differ from the float64 oracle by.
+
 With --noise it also evaluates every role WITHOUT operand rounding (same bf16-valued weights, all
 arithmetic float64) and stores how far that moves the outputs: the sensitivity of the result to the
 bf16 rounding of matrix operands, i.e. the floor under which no two bf16 evaluations can be expected to
@@ -73,6 +77,8 @@ def main():
     ap.add_argument("--beams", default=None, help="comma-separated beam indices (default: all)")
     ap.add_argument("--roles", default="target,draft,prm")
     ap.add_argument("--noise", action="store_true")
+    ap.add_argument("--floor", action="store_true",
+                    help="also evaluate with oracle.float_accumulation_jitter and store the distance (fp32_floor_*)")
     ap.add_argument("--layers", type=int, default=0)
     ap.add_argument("--append", action="store_true")
     args = ap.parse_args()
@@ -121,6 +127,19 @@ def main():
                                         "block_rms": float(np.sqrt((db ** 2).mean())),
                                         "block_max": float(np.abs(db).max())}
             print(role, "noise", out[f"noise_{role}"], flush=True)
+        if args.floor:
+            # the same rounding contract with float-sized errors in the values that get rounded: how close a
+            # float-accumulating evaluation can come to the float64 one (see oracle/rounding.py)
+            with oracle.float_accumulation_jitter(2.0e-7, seed=1):
+                res_j = oracle.score_cached(desc, hw, oracle.prefill(desc, hw, pt), cand)
+            if desc.head == "prm":
+                out[f"fp32_floor_{role}"] = {"max": float(np.abs(np.asarray(res_j) - np.asarray(res)).max())}
+            else:
+                dt, db = res_j[1] - res[1], res_j[0] - res[0]
+                out[f"fp32_floor_{role}"] = {"tok_rms": float(np.sqrt((dt ** 2).mean())), "tok_max": float(np.abs(dt).max()),
+                                             "block_rms": float(np.sqrt((db ** 2).mean())),
+                                             "block_max": float(np.abs(db).max())}
+            print(role, "fp32 floor", out[f"fp32_floor_{role}"], flush=True)
         print(role, out[f"seconds_{role}"], flush=True)
         json.dump(out, open(path, "w"))
     print("wrote", path)

@@ -265,9 +265,10 @@ def test_generation_equals_scoring_at_config_4_size():
     db = np.abs(step.out["draft"].cpu().numpy() - logp)
     print("generation vs scoring at config 4:", dict(tok_max=float(dt.max()), tok_rms=float(np.sqrt((dt ** 2).mean())),
                                                      block_max=float(db.max())), "sensitivity", noise)
-    assert dt.max() < max(2e-2, 2 * noise["tok_max"])
-    assert np.sqrt((dt ** 2).mean()) < max(5e-3, 1.5 * noise["tok_rms"])
-    assert db.max() < max(2e-2, 2 * noise["block_max"])
+    # the same bounds as the scoring parity tests: rms within one times the oracle's sensitivity, maxima as tails
+    assert np.sqrt((dt ** 2).mean()) < max(5e-3, noise["tok_rms"])
+    assert dt.max() < max(2e-2, 4.5 * noise["tok_rms"])
+    assert db.max() < max(2e-2, 3.0 * noise["block_rms"])
     step.close()
 
 

@@ -23,6 +23,7 @@ def golden(name):
     g = json.load(open(path))
     want = {k: np.asarray(v) for k, v in g.items() if k in ("target", "draft", "prm", "tok_target", "tok_draft")}
     want["noise"] = {r: g[f"noise_{r}"] for r in ("target", "draft", "prm") if f"noise_{r}" in g}
+    want["floor"] = {r: g[f"fp32_floor_{r}"] for r in ("target", "draft", "prm") if f"fp32_floor_{r}" in g}
     return want
 
 
@@ -59,57 +60,114 @@ def bf16_sensitivity(wl, want, cand=None, prefix_tokens=None):
         else:
             dt, db = res[1] - want["tok_" + role], res[0] - want[role]
             noise[role] = {"tok_rms": float(np.sqrt((dt ** 2).mean())), "tok_max": float(np.abs(dt).max()),
-                           "block_max": float(np.abs(db).max())}
+                           "block_rms": float(np.sqrt((db ** 2).mean())), "block_max": float(np.abs(db).max())}
     return noise
 
 
 def tolerances(dtype, noise, role):
-    """(token max, token rms, block max). float: 1e-5 throughout. bf16: the stated 2e-2, widened where the
-    oracle's own bf16 sensitivity shows that no bf16 evaluation can be expected to get closer."""
+    """(token max, token rms, block max, block rms). float: the stated 1e-5 throughout. bf16: the stated 2e-2 where
+    it can hold, else bounds taken from the oracle's own bf16 sensitivity (how far the float64 oracle moves when
+    operand rounding is switched off). The well-estimated statistics carry the comparison: the token rms (hundreds
+    to thousands of samples) and the block rms must not exceed ONE TIMES the oracle's, so an evaluation that is
+    further from the oracle than the oracle is from exact arithmetic fails. Maxima over a few blocks or a few
+    thousand tokens are bounded as tails of those distributions (3 block rms, 4.5 token rms) rather than by the
+    oracle's own maxima, which are single draws of the same fluctuating statistic. Whether the stated bound itself
+    was met is recorded by compare() in its statistics."""
     if dtype == "f32":
-        return TOL_F32, TOL_F32, TOL_F32
+        return TOL_F32, TOL_F32, TOL_F32, TOL_F32
     n = noise[role]
-    return max(TOL_BF16, 2 * n["tok_max"]), max(TOL_BF16 / 4, 1.5 * n["tok_rms"]), max(TOL_BF16, 2 * n["block_max"])
+    return (max(TOL_BF16, 4.5 * n["tok_rms"]), max(TOL_BF16 / 4, n["tok_rms"]), max(TOL_BF16, 3.0 * n["block_rms"]),
+            max(TOL_BF16 / 2, n["block_rms"]))
 
 
-def compare(res, want, dtype="f32", noise=None):
+def compare(res, want, dtype="f32", noise=None, stated_only=False, floor=None):
+    """Element-wise comparison of token and block log-probabilities and rewards with the oracle's.
+    stated_only: assert the stated tolerance (1e-5 float, 2e-2 bf16) with no widening at all.
+    floor: the distance between the oracle and the oracle evaluated under oracle.float_accumulation_jitter (what
+    any float-accumulating evaluation of the same rounding contract differs from the float64 one by). The GPU is
+    another such evaluation, so its distance is a draw from the same distribution: its token rms (hundreds to
+    thousands of samples) must stay within 1.35 times the floor's; the ratios of the maxima are reported.
+    Also asserts that the error has no systematic sign: |mean(GPU - oracle)| over all tokens of a role stays below
+    3 rms / sqrt(N) (plus the float32 resolution of a log-probability), which a dropped or doubled term, a shifted
+    maximum or a biased rounding would break long before it shows in the maxima."""
     stats = {}
+    stated = TOL_F32 if dtype == "f32" else TOL_BF16
     for role in ("target", "draft"):
-        tok_tol, rms_tol, blk_tol = tolerances(dtype, noise, role)
-        dt = np.abs(res["tok_" + role] - want["tok_" + role])
+        tok_tol, rms_tol, blk_tol, brms_tol = (stated,) * 4 if stated_only else tolerances(dtype, noise, role)
+        sd = (res["tok_" + role] - want["tok_" + role]).astype(np.float64)
+        dt = np.abs(sd)
         db = np.abs(res[role] - want[role])
-        stats[role] = dict(tok_max=float(dt.max()), tok_rms=float(np.sqrt((dt ** 2).mean())),
-                           block_max=float(db.max()), tol=(tok_tol, rms_tol, blk_tol))
+        rms = float(np.sqrt((dt ** 2).mean()))
+        brms = float(np.sqrt((db ** 2).mean()))
+        bias_tol = 3.0 * rms / np.sqrt(dt.size) + 2e-6
+        stats[role] = dict(tok_max=float(dt.max()), tok_rms=rms, block_max=float(db.max()), block_rms=brms,
+                           bias=float(sd.mean()), bias_tol=float(bias_tol), tol=(tok_tol, rms_tol, blk_tol, brms_tol),
+                           meets_stated=bool(dt.max() < stated and db.max() < stated))
         assert dt.max() < tok_tol, (role, stats)
-        assert np.sqrt((dt ** 2).mean()) < rms_tol, (role, stats)
+        assert rms < rms_tol, (role, stats)
         assert db.max() < blk_tol, (role, stats)
+        assert brms < brms_tol, (role, stats)
+        assert abs(sd.mean()) < bias_tol, (role, stats)
+        if floor and role in floor:
+            f = floor[role]
+            stats[role]["vs_fp32_floor"] = dict(tok_rms=rms / f["tok_rms"], tok_max=float(dt.max()) / f["tok_max"],
+                                                block_max=float(db.max()) / f["block_max"])
+            assert rms < 1.35 * f["tok_rms"], (role, stats)
     dr = np.abs(res["prm"] - want["prm"])
     stats["prm"] = float(dr.max())
-    assert dr.max() < (TOL_F32 if dtype == "f32" else TOL_BF16), stats
+    assert dr.max() < stated, stats
     return stats
 
 
-def check_selection(wl, res, tol_lp, tol_r, want=None):
+def check_selection(wl, res, want=None, delta_bound=None):
     """(1) Given the GPU's own scores the kernel's indices must equal the sequential float64 rule bit for bit.
-    (2) Against the choice made from the oracle's scores, an index may differ only where u lies within the
-    score-tolerance band eta = exp(2 delta_S) - 1 of a CDF boundary between the two indices,
-    delta_S = tol(log pi_target) + tol(log pi_draft) + beta * tol(r)."""
+    (2) Against the choice made from the oracle's scores: with delta = max_i |S_gpu,i - S_oracle,i| MEASURED per
+    (beam, beta), every selection probability moves by a factor within exp(+-2 delta), so an index may differ only
+    where u lies within eta = exp(2 delta) - 1 of one of the oracle's CDF boundaries between the two indices.
+    For eta >= 1 that band says nothing; such a (beam, beta) is counted as undetermined, and it is the caller's
+    bound on the scores (compare()) that limits delta. (3) The two selection distributions are within
+    tanh(delta_bound) of each other in total variation, delta_bound being the score tolerance the caller asserts.
+    Returns (selections that differ, undetermined ones, largest total-variation distance)."""
     u = wl.uniforms()
     idx, maxr = oracle.subsample_batch(res["target"], res["draft"], res["prm"], wl.betas, u)
     assert np.array_equal(np.asarray(idx), res["idx"])
     assert np.array_equal(np.asarray(maxr, dtype=np.float32), res["max_reward"])
     if want is None:
-        return
+        return 0, 0, 0.0
     oidx, _ = oracle.subsample_batch(want["target"], want["draft"], want["prm"], wl.betas, u)
+    differ = undetermined = 0
+    tv_max = 0.0
     for b in range(wl.B):
         for j, beta in enumerate(wl.betas):
+            s_gpu = oracle.scores(res["target"][b], res["draft"][b], res["prm"][b], beta)
+            s_or = oracle.scores(want["target"][b], want["draft"][b], want["prm"][b], beta)
+            delta = float(np.abs(np.asarray(s_gpu, dtype=np.float64) - np.asarray(s_or, dtype=np.float64)).max())
+            p_gpu = oracle.selection_probs(res["target"][b], res["draft"][b], res["prm"][b], beta)
+            p_or = oracle.selection_probs(want["target"][b], want["draft"][b], want["prm"][b], beta)
+            tv = 0.5 * float(np.abs(np.asarray(p_gpu) - np.asarray(p_or)).sum())
+            tv_max = max(tv_max, tv)
+            assert tv <= np.tanh(delta) + 1e-12, (b, j, tv, delta)
+            if delta_bound is not None:
+                assert tv <= np.tanh(delta_bound(beta)) + 1e-12, (b, j, tv, delta_bound(beta))
             kg, ko = int(res["idx"][b, j]), int(oidx[b][j])
             if kg == ko:
                 continue
-            eta = np.exp(2 * (2 * tol_lp + beta * tol_r)) - 1
-            cdf = np.cumsum(oracle.selection_probs(want["target"][b], want["draft"][b], want["prm"][b], beta))
+            differ += 1
+            eta = np.exp(2 * delta) - 1
+            if eta >= 1:
+                undetermined += 1
+                continue
+            cdf = np.cumsum(p_or)
             lo, hi = min(kg, ko), max(kg, ko)
-            assert min(abs(u[b, j] - cdf[k]) for k in range(lo, hi)) <= eta, (b, j, kg, ko)
+            assert min(abs(u[b, j] - cdf[k]) for k in range(lo, hi)) <= eta, (b, j, kg, ko, eta)
+    return differ, undetermined, tv_max
+
+
+def score_bound(dtype, noise):
+    """beta -> the bound on |S_gpu - S_oracle| that compare() enforces: block tolerances of both LMs + beta * reward's."""
+    lp = sum(tolerances(dtype, noise, r)[2] for r in ("target", "draft"))
+    tr = TOL_F32 if dtype == "f32" else TOL_BF16
+    return lambda beta: lp + beta * tr
 
 
 def run_step(wl, **kw):
@@ -125,7 +183,7 @@ def test_c1_tiny_float_matches_oracle_in_both_modes():
     step, res = run_step(wl)
     want = oracle_step(wl)
     compare(res, want)
-    check_selection(wl, res, TOL_F32, TOL_F32, want)
+    assert check_selection(wl, res, want, score_bound("f32", None))[:2] == (0, 0)
     # the definition itself (full recompute per candidate)
     blk, tok = oracle.block_logprobs_full(wl.target, HostWeights(wl.target), wl.prefix_tokens()[0], wl.candidates()[0])
     assert np.abs(res["target"][0] - blk).max() < TOL_F32
@@ -174,8 +232,7 @@ def test_ragged_shapes_several_beams_shuffled_pages(kind):
     noise = bf16_sensitivity(wl, want) if dtype == "bf16" else None
     stats = compare(res, want, dtype, noise)
     print(kind, stats)
-    blk = max(tolerances(dtype, noise, r)[2] for r in ("target", "draft"))
-    check_selection(wl, res, blk, TOL_F32 if dtype == "f32" else TOL_BF16, want)
+    print(kind, "selections (differ, undetermined, max TV):", check_selection(wl, res, want, score_bound(dtype, noise)))
     step.close()
 
 
@@ -246,10 +303,10 @@ def test_benchmark_configs_bf16_match_stored_oracle(name):
     if not all(k in want for k in ("target", "draft", "prm")):
         pytest.skip("stored oracle outputs incomplete")
     step, res = run_step(wl)
-    stats = compare(res, want, "bf16", want["noise"])
-    print(name, "GPU vs oracle:", stats, "oracle bf16 sensitivity:", want["noise"])
-    blk = max(tolerances("bf16", want["noise"], r)[2] for r in ("target", "draft"))
-    check_selection(wl, res, blk, TOL_BF16, want)
+    stats = compare(res, want, "bf16", want["noise"], floor=want["floor"])
+    print(name, "GPU vs oracle:", stats, "oracle bf16 sensitivity:", want["noise"], "fp32 floor:", want["floor"])
+    print(name, "selections (differ, undetermined, max TV):",
+          check_selection(wl, res, want, score_bound("bf16", want["noise"])))
     # properties that hold at any size: candidates sharing their first token share its log-prob exactly
     cand = wl.candidates()[0]
     for i in range(wl.n):
@@ -261,6 +318,34 @@ def test_benchmark_configs_bf16_match_stored_oracle(name):
     res2 = step.score_and_select()
     for k in ("target", "draft", "prm", "idx"):
         assert np.array_equal(res[k], res2[k]), k
+    step.close()
+
+
+@pytest.mark.parametrize("layers", [1, 2, 4])
+def test_c4_full_width_depth_series(layers):
+    """Config 4 at its full widths (d 3584, F 18944, V 152064, P 4096, n 16, L 128; draft 1.5B widths) with the
+    first 1, 2 and 4 layers of every model, against oracle outputs stored by make_oracle_golden.py --layers.
+    This is the bf16 MFMA path end to end (rotary embedding inside the QKV epilogue, K-split partial products summed
+    inside the normalisation kernel, shifted final norm, fused vocabulary head, last-token PRM shortcut). Asserted at
+    every depth: one times the oracle's own bf16 sensitivity, no systematic sign, and the float-accumulation floor
+    (see compare()); at ONE layer also the stated 2e-2 on every token with no widening. (A block is a sum of 128
+    token terms: even at one layer the oracle itself moves a block by 0.11 under float-sized jitter, so the stated
+    bound cannot hold on block level for any float-accumulating evaluation.) The printed figures are the
+    error-versus-depth curve."""
+    name = f"c4_7b_L{layers}"
+    if not os.path.exists(os.path.join(os.path.dirname(__file__), "golden", f"oracle_{name}.json")):
+        pytest.skip(f"tests/golden/oracle_{name}.json not generated")
+    base = W.get_config("c4_7b")
+    wl = W.configs.scaled(base, **{r: dataclasses.replace(m, n_layers=min(layers, m.n_layers))
+                                   for r, m in base.models().items()})
+    want = golden(name)
+    step, res = run_step(wl)
+    stats = compare(res, want, "bf16", want["noise"], floor=want["floor"])
+    if layers == 1:           # one layer: every token within the stated bound, no widening
+        assert max(stats[r]["tok_max"] for r in ("target", "draft")) < TOL_BF16, stats
+    print(name, "GPU vs oracle:", stats, "oracle bf16 sensitivity:", want["noise"], "fp32 floor:", want["floor"])
+    print(name, "selections (differ, undetermined, max TV):",
+          check_selection(wl, res, want, score_bound("bf16", want["noise"])))
     step.close()
 
 
@@ -287,7 +372,7 @@ def test_c5_batched_beams_paged_ragged_prefixes():
                     shared += 1
     assert shared > 10
     # SubSample per (beam, beta) from the GPU's own scores: bit-exact against the sequential float64 rule
-    check_selection(wl, res, TOL_BF16, TOL_BF16)
+    check_selection(wl, res)
     assert len(np.unique(res["idx"])) > 1
     # the stated subset of beams against the stored oracle outputs
     path = os.path.join(os.path.dirname(__file__), "golden", f"oracle_{name}.json")
@@ -322,7 +407,7 @@ def test_degenerate_and_boundary_shapes_bf16(P, n, L, hq, hkv, hd):
     want = oracle_step(wl)
     noise = bf16_sensitivity(wl, want)
     compare(res, want, "bf16", noise)
-    check_selection(wl, res, TOL_BF16, TOL_BF16, want)
+    check_selection(wl, res, want, score_bound("bf16", noise))
     step.close()
 
 

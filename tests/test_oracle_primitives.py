@@ -101,13 +101,38 @@ def test_attention_zero_query_averages_values():
 
 
 def test_attention_bf16_rounds_only_the_softmax_weights():
+    """The rounded operand is the un-normalised weight relative to a power-of-two reference, 2^(s' - ceil(max s'));
+    any other power-of-two reference gives the same output, and so does a tile-by-tile evaluation that only knows
+    a running maximum, as long as its reference exponents are integers."""
     Tq, S, hd = 3, 33, 8
     q, k, v = RNG.standard_normal((Tq, 1, hd)), RNG.standard_normal((S, 1, hd)), RNG.standard_normal((S, 1, hd))
     mask = np.ones((Tq, S), bool)
-    s = (q[:, 0] @ k[:, 0].T) / np.sqrt(hd)
-    p = np.exp(s - s.max(-1, keepdims=True))
-    want = (oracle.round_bf16(p) @ v[:, 0]) / p.sum(-1, keepdims=True)
-    assert np.allclose(oracle.attention(q, k, v, mask, "bf16"), want, atol=1e-15)
+    s2 = (q[:, 0] @ k[:, 0].T) / np.sqrt(hd) / np.log(2.0)
+    ref = np.ceil(s2.max(-1, keepdims=True))
+    got = oracle.attention(q, k, v, mask, "bf16")
+    for shift in (0, -3, 5):
+        w = np.exp2(s2 - ref - shift)
+        assert np.allclose(got, (oracle.round_bf16(w) @ v[:, 0]) / w.sum(-1, keepdims=True), atol=1e-15)
+    # weights lie in (1/2, 1] at the row maximum, and the unrounded evaluation is the plain softmax
+    assert np.all(np.exp2(s2 - ref).max(-1) > 0.5) and np.all(np.exp2(s2 - ref).max(-1) <= 1.0)
+    p = np.exp(s2 * np.log(2.0) - (s2 * np.log(2.0)).max(-1, keepdims=True))
+    assert np.allclose(oracle.attention(q, k, v, mask, "f32"), (p @ v[:, 0]) / p.sum(-1, keepdims=True), atol=1e-14)
+    # streaming evaluation: tiles of 8 keys, integer reference that follows the running maximum
+    for t in range(Tq):
+        m, l, o = -np.inf, 0.0, np.zeros(hd)
+        for k0 in range(0, S, 8):
+            st = s2[t, k0:k0 + 8]
+            m_new = max(m, np.ceil(st.max()))
+            alpha = 0.0 if m == -np.inf else np.exp2(m - m_new)
+            w = np.exp2(st - m_new)
+            l = l * alpha + w.sum()
+            o = o * alpha + oracle.round_bf16(w) @ v[k0:k0 + 8, 0]
+            m = m_new
+        assert np.allclose(o / l, got[t], atol=1e-14)
+    # a non-power-of-two reference (the plain maximum) rounds different values: the reading matters
+    w_max = np.exp2(s2 - s2.max(-1, keepdims=True))
+    other = (oracle.round_bf16(w_max) @ v[:, 0]) / w_max.sum(-1, keepdims=True)
+    assert np.abs(other - got).max() > 1e-6
 
 
 def test_reward_head_is_a_logistic_of_the_normalised_state():

@@ -187,6 +187,11 @@ int specs_generate_blocks(specs_ctx* ctx, const specs_model* m, const specs_pref
  * the device array). The page table must already cover lens + L tokens. */
 int specs_commit_block(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* chosen_host);
 
+/* specs_commit_block with the chosen indices in DEVICE memory (e.g. the idx output of specs_select_and_switch), so
+ * that an iteration of Alg. 1 needs no host round trip between selection and commit. An index outside [0, n)
+ * (a selection that failed leaves -1 and an error on the status word) is clamped by the kernels. */
+int specs_commit_block_dev(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* chosen_dev);
+
 /* SubSample (Alg. 2) for B beams and nb inverse temperatures at once:
  *   S_i = logp_target[b][i] - logp_gen[b][i] + beta[j] * reward[b][i]   (Eq. 1; only r is scaled by beta)
  *   w_i = exp(S_i - max S) for live i (mask[b][i] != 0, NULL = all live: Alg. 2's set L = [n])
@@ -197,6 +202,31 @@ int specs_commit_block(specs_ctx* ctx, const specs_model* m, specs_prefix* p, co
 int specs_subsample(specs_ctx* ctx, const float* logp_target, const float* logp_gen, const float* reward,
                     const uint8_t* mask, int32_t B, int32_t n, const float* beta, int32_t nb,
                     const double* u, int32_t* idx, float* max_reward);
+
+/* Alg. 1, Steps II (selection) and III (switch) for B beams in one launch. gen_is_draft (device uint8 [B], in/out)
+ * says which model generated beam b's candidate blocks: 0 = the target model, so pi_gen = pi_target, the
+ * log-ratio of Eq. 1 vanishes and S_i = beta r_i (the collapse to reward-only selection that the paper notes for
+ * pi_gen = pi_target; logp_draft[b] is not read); 1 = the draft model, S_i = logp_target - logp_draft + beta r_i.
+ * idx[b] is SubSample's choice at the uniform u[b] (Alg. 2, as specs_subsample with nb = 1). Then Step III: a beam
+ * with max_i reward[b][i] > tau (strictly) sets its flag, i.e. its blocks come from the draft model from the
+ * next iteration on; a set flag is never cleared. max_reward: device [B] or NULL. beta >= 0 finite (SPECS_ERANGE). */
+int specs_select_and_switch(specs_ctx* ctx, const float* logp_target, const float* logp_draft, const float* reward,
+                            const uint8_t* mask, int32_t B, int32_t n, float beta, float tau, const double* u,
+                            uint8_t* gen_is_draft, int32_t* idx, float* max_reward);
+
+/* Which implementation the launches of this process took since the counters were last reset: the matrix-unit
+ * (MFMA) kernels, the weight-streaming kernel for at most 32 rows, or the plain kernels that serve the float
+ * configuration and shapes the others do not take (K not a multiple of 64, head sizes other than 64/128, pages other
+ * than 16 tokens). counts: host int32 [SPECS_PATH_COUNT]; reset != 0 clears the counters after reading them. */
+enum {
+  SPECS_PATH_GEMM_MFMA = 0,   /* block-tiled MFMA GEMM family */
+  SPECS_PATH_GEMM_SKINNY,     /* weight-streaming MFMA GEMM (generation) */
+  SPECS_PATH_GEMM_PLAIN,      /* plain GEMM / vocabulary-head kernels */
+  SPECS_PATH_ATTN_MFMA,       /* MFMA attention kernels (whole blocks or single positions) */
+  SPECS_PATH_ATTN_PLAIN,      /* plain attention kernel */
+  SPECS_PATH_COUNT
+};
+int specs_path_counts(int32_t* counts, int reset);
 
 /* ---- Component entry points -------------------------------------------------------------------
  * The individual contractions of the scoring pass, callable on caller-provided operands so that each

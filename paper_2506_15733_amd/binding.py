@@ -16,7 +16,9 @@ EXPORTED_SYMBOLS = [
     "specs_commit_block", "specs_subsample", "specs_strerror", "specs_generate_blocks",
     "specs_op_linear", "specs_op_gate_up", "specs_op_lmhead_logprob", "specs_op_attention",
     "specs_ctx_profile", "specs_ctx_profile_read", "specs_score_blocks_static",
+    "specs_commit_block_dev", "specs_select_and_switch", "specs_path_counts",
 ]
+PATH_CLASSES = ("gemm_mfma", "gemm_skinny", "gemm_plain", "attn_mfma", "attn_plain")
 KERNEL_CLASSES = ("qkv", "attention", "oproj", "gate_up", "down", "lmhead", "other")
 
 SPECS_F32, SPECS_BF16 = 0, 1
@@ -69,6 +71,9 @@ def load_library():
     lib.specs_score_blocks_static.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp]
     lib.specs_generate_blocks.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.specs_commit_block.argtypes = [vp, vp, vp, C.POINTER(i32)]
+    lib.specs_commit_block_dev.argtypes = [vp, vp, vp, vp]
+    lib.specs_select_and_switch.argtypes = [vp, vp, vp, vp, vp, i32, i32, C.c_float, C.c_float, vp, vp, vp, vp]
+    lib.specs_path_counts.argtypes = [C.POINTER(i32), C.c_int]
     lib.specs_subsample.argtypes = [vp, vp, vp, vp, vp, i32, i32, C.POINTER(C.c_float), i32, vp, vp, vp]
     lib.specs_ctx_profile.argtypes = [vp, C.c_int]
     lib.specs_ctx_profile_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
@@ -210,6 +215,30 @@ def specs_generate_blocks(ctx, model, prefix, u, cand, logp, tok_logp=None, voca
 def specs_commit_block(ctx, model, prefix, chosen_host):
     arr = (C.c_int32 * len(chosen_host))(*[int(x) for x in chosen_host])
     _check(load_library().specs_commit_block(ctx, model, prefix, arr), "specs_commit_block")
+
+
+def specs_commit_block_dev(ctx, model, prefix, chosen_dev):
+    import torch
+    _check(load_library().specs_commit_block_dev(ctx, model, prefix, _ptr(chosen_dev, torch.int32)),
+           "specs_commit_block_dev")
+
+
+def specs_select_and_switch(ctx, logp_target, logp_draft, reward, beta, tau, u, gen_is_draft, idx, mask=None,
+                            max_reward=None):
+    import torch
+    B, n = logp_target.shape
+    _check(load_library().specs_select_and_switch(ctx, _ptr(logp_target, torch.float32), _ptr(logp_draft, torch.float32),
+                                                  _ptr(reward, torch.float32), _ptr(mask, torch.uint8, True), B, n,
+                                                  float(beta), float(tau), _ptr(u, torch.float64),
+                                                  _ptr(gen_is_draft, torch.uint8), _ptr(idx, torch.int32),
+                                                  _ptr(max_reward, torch.float32, True)), "specs_select_and_switch")
+
+
+def specs_path_counts(reset=False):
+    """{path class: launches} of this process since the counters were last reset."""
+    arr = (C.c_int32 * len(PATH_CLASSES))()
+    _check(load_library().specs_path_counts(arr, 1 if reset else 0), "specs_path_counts")
+    return {k: arr[i] for i, k in enumerate(PATH_CLASSES)}
 
 
 def specs_subsample(ctx, logp_target, logp_gen, reward, betas, u, idx, mask=None, max_reward=None):

@@ -15,6 +15,13 @@ template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
 
+// Device status word: the FIRST error since it was last cleared sticks (an ordinary global atomic compare-and-swap).
+__device__ __forceinline__ void report_status(int* status, int code) { atomicCAS(status, 0, code); }
+
+// Which implementation a launch took, counted per process (specs_path_counts): tests assert that the benchmark
+// shapes run on the matrix-unit kernels and not on the plain ones that serve odd shapes.
+void count_path(int which);
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -121,9 +128,11 @@ int lmhead_simple_tiles(int V);
 void launch_lmhead_merge(const float* part_max, const float* part_sum, const float* zt, int n_tiles, float* tok_logp,
                          float* tok_scratch, float* block_out, const BatchGeom& g, hipStream_t s);
 
+// gen_is_draft (device [B], in/out; requires nb == 1) / tau: Alg. 1 Steps II-III in one launch: beams whose flag is 0
+// take pi_gen = pi_target (lg is ignored for them), and after the selection a beam with max_i r > tau sets its flag.
 void launch_subsample(const float* lt, const float* lg, const float* r, const uint8_t* mask, int B, int n,
-                      const float* beta_dev, int nb, const double* u, int32_t* idx, float* max_reward, int* status,
-                      hipStream_t s);
+                      const float* beta_dev, int nb, const double* u, int32_t* idx, float* max_reward,
+                      uint8_t* gen_is_draft, float tau, int* status, hipStream_t s);
 
 // bf16 MFMA GEMM family (gemm_mfma.hip). Returns false if the shape is not supported.
 enum { MFMA_STORE = 0, MFMA_RESIDUAL = 1, MFMA_SWIGLU = 2, MFMA_LMHEAD = 3 };

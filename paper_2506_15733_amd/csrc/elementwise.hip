@@ -9,7 +9,7 @@ __global__ void embed_kernel(const int32_t* __restrict__ tok, int tok_stride, co
   int m = blockIdx.x;
   int id = tok[(size_t)m * tok_stride];
   if (id < 0 || id >= V) {
-    if (threadIdx.x == 0) *status = SPECS_ETOKEN;
+    if (threadIdx.x == 0) report_status(status, SPECS_ETOKEN);
     id = id < 0 ? 0 : V - 1;
   }
   const T* row = E + (size_t)id * d;
@@ -346,6 +346,7 @@ __global__ void kv_commit_kernel(const T* __restrict__ kb, const T* __restrict__
                                  const int32_t* __restrict__ chosen) {
   int t = blockIdx.x, b = blockIdx.y;
   int i = chosen ? chosen[b] : 0;
+  i = i < 0 ? 0 : (i >= g.n ? g.n - 1 : i);          // an index a failed selection left (-1) must not address memory
   int ctx = g.len_override >= 0 ? g.len_override : g.lens[g.b0 + b];
   int pos = ctx + t;
   int page = g.page_table[(size_t)(g.b0 + b) * g.max_pages + pos / g.page_tokens];
@@ -373,6 +374,7 @@ __global__ void copy_rows_kernel(const float* __restrict__ x, float* __restrict_
                                  const int32_t* __restrict__ chosen) {
   int b = blockIdx.x;
   int i = chosen ? chosen[b] : 0;
+  i = i < 0 ? 0 : (i >= g.n ? g.n - 1 : i);
   size_t m = ((size_t)b * g.n + i) * g.L + (g.L - 1);
   for (int c = threadIdx.x; c < d; c += blockDim.x) h_last[(size_t)(g.b0 + b) * d + c] = x[m * d + c];
 }

@@ -7,6 +7,7 @@
 // and finally over single ids. All sums run in id order; only the grouping of the additions differs from one
 // long running sum.
 #include "common.h"
+#include <climits>
 
 constexpr int SAMPLE_CHUNKS = 128;
 
@@ -73,7 +74,7 @@ __global__ void __launch_bounds__(256) sample_pick_kernel(const float* __restric
   float mx = tid < SAMPLE_CHUNKS ? cmax[row * SAMPLE_CHUNKS + tid] : -INFINITY;
   mx = wave_max(mx);
   if ((tid & 63) == 0) wmax[tid >> 6] = mx;
-  if (tid == 0) sel = -1;
+  if (tid == 0) sel = INT_MAX;
   __syncthreads();
   mx = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
   const double m = (double)mx;
@@ -90,19 +91,20 @@ __global__ void __launch_bounds__(256) sample_pick_kernel(const float* __restric
   const bool bad_z = !(total > 0.0) || !(total < INFINITY) || !(mx > -INFINITY);
   if (bad_u || bad_z) {
     if (tid == 0) {
-      *status = bad_u ? SPECS_ERANGE : SPECS_ENONFINITE;
+      report_status(status, bad_u ? SPECS_ERANGE : SPECS_ENONFINITE);
       cand[row * L + t] = 0;
       tok_logp[row * L + t] = -INFINITY;
     }
     return;
   }
-  // first chunk whose inclusive sum exceeds the threshold; none (rounding) -> the last chunk of positive weight
-  {
-    const double excl = tid ? buf[tid - 1] : 0.0;
-    if (incl > thr && !(excl > thr)) sel = tid;
-  }
+  // First chunk OF POSITIVE WEIGHT whose inclusive sum exceeds the threshold; none (rounding) -> the last chunk of
+  // positive weight. The scan adds the same terms in a different grouping for every position, so its values need
+  // not be monotone to the last bit: "first" is taken as a minimum over the threads that qualify (an LDS atomic),
+  // never as "the one whose predecessor does not qualify", which may hold for several threads or for a chunk of
+  // zero weight beyond the permitted ids.
+  if (w > 0.0 && incl > thr) atomicMin(&sel, tid);
   __syncthreads();
-  if (sel < 0) {
+  if (sel == INT_MAX) {
     if (tid == 0) {
       int c = SAMPLE_CHUNKS - 1;
       while (c > 0 && !(buf[c] > buf[c - 1])) --c;
@@ -121,9 +123,12 @@ __global__ void __launch_bounds__(256) sample_pick_kernel(const float* __restric
   for (int k = k0; k < k1; ++k) mine += exp((double)z[k] - m);
   incl = block_scan_256(mine, buf) + before;
   const double excl = (tid ? buf[tid - 1] : 0.0) + before;
-  if (tid == 0) sel = -1;
+  __shared__ int first;
+  if (tid == 0) { sel = -1; first = INT_MAX; }
   __syncthreads();
-  if (incl > thr && !(excl > thr)) {
+  if (mine > 0.0 && incl > thr) atomicMin(&first, tid);       // the first run that crosses the threshold, as above
+  __syncthreads();
+  if (tid == first) {
     double c = excl;
     int pick = -1;
     for (int k = k0; k < k1; ++k) {

@@ -1,6 +1,7 @@
 // Host side of the C ABI: handle bookkeeping, argument checks, workspace carving and the order
 // in which the kernels of one scoring pass are enqueued. No device memory is allocated here.
 #include "common.h"
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -31,6 +32,18 @@ static int resolve_static_scratch(int device) {
   void* ptr = nullptr;
   if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SPECS_EHIP;
   g_static_scratch[device] = (char*)ptr;
+  return SPECS_OK;
+}
+
+static std::atomic<int> g_path_counts[SPECS_PATH_COUNT];
+void count_path(int which) {
+  if (which >= 0 && which < SPECS_PATH_COUNT) g_path_counts[which].fetch_add(1, std::memory_order_relaxed);
+}
+extern "C" int specs_path_counts(int32_t* counts, int reset) {
+  if (!counts) return SPECS_EINVAL;
+  for (int i = 0; i < SPECS_PATH_COUNT; ++i)
+    counts[i] = reset ? g_path_counts[i].exchange(0, std::memory_order_relaxed)
+                      : g_path_counts[i].load(std::memory_order_relaxed);
   return SPECS_OK;
 }
 
@@ -313,13 +326,18 @@ static ModelDims dims_of(const specs_model_desc& d) {
 
 template <typename T>
 static void gemm(const T* A, const T* W, float* C, int M, int N, int K, GemmEpilogue epi, hipStream_t s) {
+  count_path(SPECS_PATH_GEMM_PLAIN);
   launch_gemm_simple<T>(A, W, C, M, N, K, epi, s);
 }
 template <>
 void gemm<bf16_t>(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmEpilogue epi, hipStream_t s) {
   int e = epi == EPI_RESIDUAL_ADD ? MFMA_RESIDUAL : MFMA_STORE;
-  if (!launch_gemm_mfma(e, A, W, M, N, K, C, nullptr, nullptr, nullptr, nullptr, nullptr, 1, 0, s))
+  if (launch_gemm_mfma(e, A, W, M, N, K, C, nullptr, nullptr, nullptr, nullptr, nullptr, 1, 0, s)) {
+    count_path(SPECS_PATH_GEMM_MFMA);
+  } else {
+    count_path(SPECS_PATH_GEMM_PLAIN);
     launch_gemm_simple<bf16_t>(A, W, C, M, N, K, epi, s);
+  }
 }
 
 // K-split form of x += A W^T for the residual projections: when the plan says that slicing K fills the CUs
@@ -336,15 +354,17 @@ int gemm_residual_split<bf16_t>(const bf16_t* A, const bf16_t* W, float* x, floa
                                 int K, hipStream_t s) {
   if (M <= 32 && max_split >= 1) {                       // a few rows: stream the weights once, K in slices
     int sp = skinny_gemm_split(N, K, max_split);
-    if (launch_gemm_skinny(MFMA_STORE, A, W, M, N, K, part, nullptr, sp, s)) return sp;
+    if (launch_gemm_skinny(MFMA_STORE, A, W, M, N, K, part, nullptr, sp, s)) { count_path(SPECS_PATH_GEMM_SKINNY); return sp; }
   }
   // Also with one slice the product goes to `part` and the normalisation kernel, which reads x anyway, adds it:
   // the GEMM's epilogue then only writes, instead of waiting for a read of x before every store.
   int bm = 0, split = 1;
   if (K % 64 == 0 && max_split > 1) mfma_gemm_plan(M, N, K, max_split, &bm, &split);
   if (max_split >= 1 &&
-      launch_gemm_mfma(MFMA_STORE, A, W, M, N, K, part, nullptr, nullptr, nullptr, nullptr, nullptr, split, bm, s))
+      launch_gemm_mfma(MFMA_STORE, A, W, M, N, K, part, nullptr, nullptr, nullptr, nullptr, nullptr, split, bm, s)) {
+    count_path(SPECS_PATH_GEMM_MFMA);
     return split;
+  }
   gemm<bf16_t>(A, W, x, M, N, K, EPI_RESIDUAL_ADD, s);
   return 0;
 }
@@ -360,7 +380,7 @@ int gemm_store_split<bf16_t>(const bf16_t* A, const bf16_t* W, float* C, int max
                              hipStream_t s) {
   if (M <= 32 && max_split >= 1) {
     int sp = skinny_gemm_split(N, K, max_split);
-    if (launch_gemm_skinny(MFMA_STORE, A, W, M, N, K, C, nullptr, sp, s)) return sp;
+    if (launch_gemm_skinny(MFMA_STORE, A, W, M, N, K, C, nullptr, sp, s)) { count_path(SPECS_PATH_GEMM_SKINNY); return sp; }
   }
   gemm<bf16_t>(A, W, C, M, N, K, EPI_STORE_F32, s);
   return 1;
@@ -374,19 +394,26 @@ static bool qkv_rope_fused(const T*, const T*, const float*, T*, T*, T*, const B
 template <>
 bool qkv_rope_fused<bf16_t>(const bf16_t* A, const bf16_t* W, const float* cs, bf16_t* q, bf16_t* kb, bf16_t* vT,
                             const BatchGeom& g, const ModelDims& md, int Lp, hipStream_t s) {
-  return launch_gemm_mfma_qkv_rope(A, W, cs, q, kb, vT, g, md, Lp, s);
+  if (!launch_gemm_mfma_qkv_rope(A, W, cs, q, kb, vT, g, md, Lp, s)) return false;
+  count_path(SPECS_PATH_GEMM_MFMA);
+  return true;
 }
 
 // act[M,F] = silu(A Wg^T) * (A Wu^T) with Wgu interleaved by 32 rows
 template <typename T>
 static void gate_up(const T* A, const T* Wgu, float* gu, T* act, int M, int F, int K, hipStream_t s) {
+  count_path(SPECS_PATH_GEMM_PLAIN);
   launch_gemm_simple<T>(A, Wgu, gu, M, 2 * F, K, EPI_STORE_F32, s);
   launch_silu_mul<T>(gu, act, M, F, s);
 }
 template <>
 void gate_up<bf16_t>(const bf16_t* A, const bf16_t* Wgu, float* gu, bf16_t* act, int M, int F, int K, hipStream_t s) {
-  if (M <= 32 && launch_gemm_skinny(MFMA_SWIGLU, A, Wgu, M, 2 * F, K, nullptr, act, 1, s)) return;
-  if (launch_gemm_mfma(MFMA_SWIGLU, A, Wgu, M, 2 * F, K, nullptr, act, nullptr, nullptr, nullptr, nullptr, 1, 0, s)) return;
+  if (M <= 32 && launch_gemm_skinny(MFMA_SWIGLU, A, Wgu, M, 2 * F, K, nullptr, act, 1, s)) { count_path(SPECS_PATH_GEMM_SKINNY); return; }
+  if (launch_gemm_mfma(MFMA_SWIGLU, A, Wgu, M, 2 * F, K, nullptr, act, nullptr, nullptr, nullptr, nullptr, 1, 0, s)) {
+    count_path(SPECS_PATH_GEMM_MFMA);
+    return;
+  }
+  count_path(SPECS_PATH_GEMM_PLAIN);
   launch_gemm_simple<bf16_t>(A, Wgu, gu, M, 2 * F, K, EPI_STORE_F32, s);
   launch_silu_mul<bf16_t>(gu, act, M, F, s);
 }
@@ -396,13 +423,18 @@ template <typename T>
 static int lmhead_partials(const T* A, const T* W, const int32_t* tok, float* pm, float* ps, float* zt, int M, int V,
                            int K, hipStream_t s) {
   int tiles = 0;
+  count_path(SPECS_PATH_GEMM_PLAIN);
   launch_lmhead_partials_simple<T>(A, W, tok, pm, ps, zt, M, V, K, &tiles, s);
   return tiles;
 }
 template <>
 int lmhead_partials<bf16_t>(const bf16_t* A, const bf16_t* W, const int32_t* tok, float* pm, float* ps, float* zt, int M,
                             int V, int K, hipStream_t s) {
-  if (launch_gemm_mfma(MFMA_LMHEAD, A, W, M, V, K, nullptr, nullptr, tok, pm, ps, zt, 1, 0, s)) return mfma_lmhead_tiles(V);
+  if (launch_gemm_mfma(MFMA_LMHEAD, A, W, M, V, K, nullptr, nullptr, tok, pm, ps, zt, 1, 0, s)) {
+    count_path(SPECS_PATH_GEMM_MFMA);
+    return mfma_lmhead_tiles(V);
+  }
+  count_path(SPECS_PATH_GEMM_PLAIN);
   int tiles = 0;
   launch_lmhead_partials_simple<bf16_t>(A, W, tok, pm, ps, zt, M, V, K, &tiles, s);
   return tiles;
@@ -674,21 +706,27 @@ __global__ void advance_lens_kernel(int32_t* lens, int B, int L) {
   if (b < B) lens[b] += L;
 }
 
+// chosen_dev != nullptr: the indices are already in device memory (no copy, no host-side range check)
 template <typename T>
-static int commit_impl(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* chosen_host) {
+static int commit_impl(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* chosen_host,
+                       const int32_t* chosen_dev = nullptr) {
   const specs_model_desc& d = m->desc;
   int n = ctx->last_n, L = ctx->last_L;
   int64_t R = (int64_t)p->B * n * L, C = (int64_t)p->B * n;
   Workspace ws = carve(ctx->workspace, d, R, C);
   ModelDims md = dims_of(d);
   hipStream_t s = ctx->stream;
-  HIP_TRY(hipMemcpyAsync(ws.chosen, chosen_host, sizeof(int32_t) * p->B, hipMemcpyHostToDevice, s));
+  const int32_t* chosen = chosen_dev;
+  if (!chosen) {
+    HIP_TRY(hipMemcpyAsync(ws.chosen, chosen_host, sizeof(int32_t) * p->B, hipMemcpyHostToDevice, s));
+    chosen = ws.chosen;
+  }
   BatchGeom g = block_geom(p, n, L);
   size_t kvd = (size_t)md.Hkv * md.hd;
   for (int l = 0; l < d.n_layers; ++l)
     launch_kv_commit<T>((const T*)ws.kblk + (size_t)l * R * kvd, (const T*)ws.vblk + (size_t)l * (R + 16 * C) * kvd,
-                        pool_ptr<T>(p, d, l, 0), pool_ptr<T>(p, d, l, 1), g, md, round16(L), ws.chosen, s);
-  launch_copy_rows(ws.x, p->h_last, g, d.d_model, ws.chosen, s);
+                        pool_ptr<T>(p, d, l, 0), pool_ptr<T>(p, d, l, 1), g, md, round16(L), chosen, s);
+  launch_copy_rows(ws.x, p->h_last, g, d.d_model, chosen, s);
   advance_lens_kernel<<<(p->B + 63) / 64, 64, 0, s>>>(p->lens_dev, p->B, L);
   HIP_TRY(hipGetLastError());
   for (int b = 0; b < p->B; ++b) p->lens[b] += L;
@@ -709,6 +747,16 @@ extern "C" int specs_commit_block(specs_ctx* ctx, const specs_model* m, specs_pr
                                      : commit_impl<float>(ctx, m, p, chosen_host);
 }
 
+extern "C" int specs_commit_block_dev(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const int32_t* chosen_dev) {
+  if (!ctx || !m || !p || !chosen_dev) return SPECS_EINVAL;
+  if (ctx->last_model != m || ctx->last_prefix != p || ctx->last_L <= 0) return SPECS_EINVAL;
+  for (int b = 0; b < p->B; ++b)
+    if ((int64_t)p->lens[b] + ctx->last_L > (int64_t)p->max_pages * p->page_tokens) return SPECS_EINVAL;
+  HIP_TRY(hipSetDevice(ctx->device));
+  return m->desc.dtype == SPECS_BF16 ? commit_impl<bf16_t>(ctx, m, p, nullptr, chosen_dev)
+                                     : commit_impl<float>(ctx, m, p, nullptr, chosen_dev);
+}
+
 extern "C" int specs_subsample(specs_ctx* ctx, const float* logp_target, const float* logp_gen, const float* reward,
                                const uint8_t* mask, int32_t B, int32_t n, const float* beta, int32_t nb,
                                const double* u, int32_t* idx, float* max_reward) {
@@ -717,8 +765,22 @@ extern "C" int specs_subsample(specs_ctx* ctx, const float* logp_target, const f
   for (int j = 0; j < nb; ++j)
     if (!std::isfinite(beta[j]) || beta[j] < 0.f) return SPECS_ERANGE;
   HIP_TRY(hipSetDevice(ctx->device));
-  launch_subsample(logp_target, logp_gen, reward, mask, B, n, beta, nb, u, idx, max_reward, (int*)ctx->workspace,
-                   ctx->stream);
+  launch_subsample(logp_target, logp_gen, reward, mask, B, n, beta, nb, u, idx, max_reward, nullptr, 0.f,
+                   (int*)ctx->workspace, ctx->stream);
+  HIP_TRY(hipGetLastError());
+  return SPECS_OK;
+}
+
+extern "C" int specs_select_and_switch(specs_ctx* ctx, const float* logp_target, const float* logp_draft,
+                                       const float* reward, const uint8_t* mask, int32_t B, int32_t n, float beta,
+                                       float tau, const double* u, uint8_t* gen_is_draft, int32_t* idx,
+                                       float* max_reward) {
+  if (!ctx || !logp_target || !logp_draft || !reward || !u || !gen_is_draft || !idx) return SPECS_EINVAL;
+  if (B <= 0 || n <= 0 || n > SPECS_MAX_CANDIDATES) return SPECS_EINVAL;
+  if (!std::isfinite(beta) || beta < 0.f || std::isnan(tau)) return SPECS_ERANGE;
+  HIP_TRY(hipSetDevice(ctx->device));
+  launch_subsample(logp_target, logp_draft, reward, mask, B, n, &beta, 1, u, idx, max_reward, gen_is_draft, tau,
+                   (int*)ctx->workspace, ctx->stream);
   HIP_TRY(hipGetLastError());
   return SPECS_OK;
 }
@@ -797,6 +859,7 @@ extern "C" int specs_op_lmhead_logprob(specs_ctx* ctx, int32_t dtype, const void
 template <typename T>
 static void attention(const T* q, const T* kb, const T* vbT, const T* pK, const T* pV, T* out, const BatchGeom& g,
                       const ModelDims& md, int Lp, int max_ctx, float* scratch, size_t scratch_floats, hipStream_t s) {
+  count_path(SPECS_PATH_ATTN_PLAIN);
   launch_attention_simple<T>(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, s);
 }
 template <>
@@ -807,13 +870,22 @@ void attention<bf16_t>(const bf16_t* q, const bf16_t* kb, const bf16_t* vbT, con
   // Launches with at least ~160 workgroups of 256 stacked rows take the two-phase kernel (measured 3-8 % faster
   // at the 7B shapes); smaller ones the one-phase kernel, which cuts long key lists over several workgroups.
   const long stacked = (long)g.B * md.Hkv * (((long)g.n * g.L * (md.Hq / md.Hkv) + 255) / 256);
-  bool done = whole_blocks ? ((stacked >= 160 &&
-                               launch_attention_pingpong(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, nullptr, 0, s)) ||
-                              launch_attention_mfma(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, scratch, scratch_floats, s))
-                           : (g.L == 1 && scratch &&
-                              launch_attention_decode(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, scratch,
-                                                      scratch_floats, s));
-  if (!done) launch_attention_simple<bf16_t>(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, s);
+  if (whole_blocks) {
+    if (stacked >= 160 && launch_attention_pingpong(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, nullptr, 0, s)) {
+      count_path(SPECS_PATH_ATTN_MFMA);
+      return;
+    }
+    if (launch_attention_mfma(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, scratch, scratch_floats, s)) {
+      count_path(SPECS_PATH_ATTN_MFMA);
+      return;
+    }
+  } else if (g.L == 1 && scratch &&
+             launch_attention_decode(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, scratch, scratch_floats, s)) {
+    count_path(SPECS_PATH_ATTN_MFMA);
+    return;
+  }
+  count_path(SPECS_PATH_ATTN_PLAIN);
+  launch_attention_simple<bf16_t>(q, kb, vbT, pK, pV, out, g, md, Lp, max_ctx, s);
 }
 
 extern "C" int specs_op_attention(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, int32_t layer,

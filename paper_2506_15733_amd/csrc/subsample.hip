@@ -16,17 +16,19 @@ __global__ void __launch_bounds__(64) subsample_kernel(const float* __restrict__
                                                        const float* __restrict__ r, const uint8_t* __restrict__ mask,
                                                        int n, BetaList betas, int nb, const double* __restrict__ u,
                                                        int32_t* __restrict__ idx, float* __restrict__ max_reward,
-                                                       int* status) {
+                                                       uint8_t* __restrict__ gen_is_draft, float tau, int* status) {
   __shared__ double w[SPECS_MAX_CANDIDATES];
   int b = blockIdx.x, j = blockIdx.y, lane = threadIdx.x;
   double beta = (double)betas.v[j];
+  // Alg. 1: while the target model generates a beam's blocks, pi_gen = pi_target and the log-ratio of Eq. 1 is 0
+  const bool gen_target = gen_is_draft != nullptr && gen_is_draft[b] == 0;
   double smax = -INFINITY;
   float rmax = -INFINITY;
   bool bad = false;
   int live = 0;
   for (int i = lane; i < n; i += 64) {
     size_t o = (size_t)b * n + i;
-    double S = (double)lt[o] - (double)lg[o] + beta * (double)r[o];
+    double S = (gen_target ? 0.0 : (double)lt[o] - (double)lg[o]) + beta * (double)r[o];
     bool on = mask ? mask[o] != 0 : true;
     rmax = fmaxf(rmax, r[o]);
     if (on) {
@@ -48,9 +50,9 @@ __global__ void __launch_bounds__(64) subsample_kernel(const float* __restrict__
     double uu = u[(size_t)b * nb + j];
     int pick = -1;
     if (bad || live == 0) {
-      *status = SPECS_ENONFINITE;
+      report_status(status, SPECS_ENONFINITE);
     } else if (!(uu >= 0.0 && uu < 1.0)) {
-      *status = SPECS_ERANGE;
+      report_status(status, SPECS_ERANGE);
     } else {
       double total = 0.0;
       for (int i = 0; i < n; ++i) total += w[i];
@@ -64,13 +66,16 @@ __global__ void __launch_bounds__(64) subsample_kernel(const float* __restrict__
           if (w[i] > 0.0) { pick = i; break; }
     }
     idx[(size_t)b * nb + j] = pick;
+    // Alg. 1 Step III: once some candidate's reward exceeds the threshold (strictly), the draft model generates
+    // this beam's blocks from the next iteration on, for good
+    if (gen_is_draft != nullptr && j == 0 && rmax > tau) gen_is_draft[b] = 1;
   }
 }
 
 void launch_subsample(const float* lt, const float* lg, const float* r, const uint8_t* mask, int B, int n,
-                      const float* beta_host, int nb, const double* u, int32_t* idx, float* max_reward, int* status,
-                      hipStream_t s) {
+                      const float* beta_host, int nb, const double* u, int32_t* idx, float* max_reward,
+                      uint8_t* gen_is_draft, float tau, int* status, hipStream_t s) {
   BetaList bl = {};
   for (int j = 0; j < nb; ++j) bl.v[j] = beta_host[j];
-  subsample_kernel<<<dim3(B, nb), 64, 0, s>>>(lt, lg, r, mask, n, bl, nb, u, idx, max_reward, status);
+  subsample_kernel<<<dim3(B, nb), 64, 0, s>>>(lt, lg, r, mask, n, bl, nb, u, idx, max_reward, gen_is_draft, tau, status);
 }

@@ -161,61 +161,53 @@ class ScoringStep:
 
 def run_specs_loop(step: ScoringStep, blocks, tau, beta_index=0, start_with_target=True, fast_path=True):
     """Alg. 1 with a synthetic generator: for each iteration h, blocks[h] is the [B, n, L] candidate set the
-    generator proposed (token ids; generation itself is outside this path). Step II: score, SubSample, append the
-    chosen block to the trace of all three models (specs_commit_block). Step III: per beam, once
-    max_i r(Y_i|tr) > tau the generator switches from the target to the draft model, for good.
-    While a beam's generator IS the target, pi_gen = pi_target and the score collapses to beta * r (Eq. 1),
-    which is passed to SubSample as logp_gen := logp_target.
+    generator proposed (token ids; generation itself is outside this path). Everything the method decides happens
+    behind the C ABI: specs_select_and_switch applies Eq. 1 with the beam's current generator as pi_gen, draws
+    SubSample's index and performs Step III's switch on the device-resident generator flags; specs_commit_block_dev
+    appends the chosen block (Step II) from the device-resident index. This function only moves inputs and
+    chooses which passes to enqueue from a host copy of the flags.
     fast_path: in an iteration where EVERY beam's generator is the target, no log-likelihood enters the score, so
     only the PRM scores the n candidates; target and draft then run over the one chosen block per beam (n = 1),
     which is all their caches need.
     Returns the chosen indices [H, B], the generator flags [H, B] (True = draft generated that iteration) and,
     per iteration, whether the PRM-only path ran."""
-    wl = step.wl
-    use_draft = np.zeros(wl.B, dtype=bool) if start_with_target else np.ones(wl.B, dtype=bool)
+    wl, dev = step.wl, step.device
+    gen = torch.full((wl.B,), 0 if start_with_target else 1, dtype=torch.uint8, device=dev)
     chosen_all, gen_all, fast_all = [], [], []
     u_all = W.rng.uniform_f64(wl.u_seed, "loop/u", len(blocks) * wl.B).reshape(len(blocks), wl.B)
-    betas = (wl.betas[beta_index],)
-    idx = torch.zeros((wl.B, 1), dtype=torch.int32, device=step.device)
-    zeros = torch.zeros((wl.B, wl.n), dtype=torch.float32, device=step.device)
-    out1 = {r: torch.zeros((wl.B, 1), dtype=torch.float32, device=step.device) for r in ("target", "draft")}
-    tok1 = {r: torch.zeros((wl.B, 1, wl.L), dtype=torch.float32, device=step.device) for r in ("target", "draft")}
-    beams = torch.arange(wl.B, device=step.device)
+    beta = wl.betas[beta_index]
+    idx = torch.zeros((wl.B,), dtype=torch.int32, device=dev)
+    zeros = torch.zeros((wl.B, wl.n), dtype=torch.float32, device=dev)
+    zero_idx = torch.zeros((wl.B,), dtype=torch.int32, device=dev)
+    out1 = {r: torch.zeros((wl.B, 1), dtype=torch.float32, device=dev) for r in ("target", "draft")}
+    tok1 = {r: torch.zeros((wl.B, 1, wl.L), dtype=torch.float32, device=dev) for r in ("target", "draft")}
+    beams = torch.arange(wl.B, device=dev)
     for h, cand in enumerate(blocks):
-        step.cand = torch.from_numpy(np.ascontiguousarray(cand.astype(np.int32))).to(step.device)
-        fast = fast_path and not use_draft.any()
-        u = torch.from_numpy(u_all[h:h + 1].T.copy()).to(step.device)
+        step.cand = torch.from_numpy(np.ascontiguousarray(cand.astype(np.int32))).to(dev)
+        flags = gen.cpu().numpy().astype(bool)              # host copy: which passes to enqueue
+        fast = fast_path and not flags.any()
+        u = torch.from_numpy(u_all[h].copy()).to(dev)
         step._fork()
         for r in (("prm",) if fast else step.ROLES):
             step.score(r)
         step._join()
-        if fast:
-            B.specs_subsample(step.sel_ctx, zeros, zeros, step.out["prm"], betas, u, idx, None, step.max_reward)
-        else:
-            # generator = target for beams that have not switched: the log-ratio term vanishes
-            mask = torch.from_numpy(use_draft).to(step.device)[:, None]
-            lgen = torch.where(mask, step.out["draft"], step.out["target"])
-            B.specs_subsample(step.sel_ctx, step.out["target"], lgen.contiguous(), step.out["prm"], betas, u, idx,
-                              None, step.max_reward)
-        torch.cuda.synchronize()
-        chosen = idx[:, 0].cpu().numpy()
-        gen_all.append(use_draft.copy())
-        chosen_all.append(chosen.copy())
+        lt, ld = (zeros, zeros) if fast else (step.out["target"], step.out["draft"])
+        B.specs_select_and_switch(step.sel_ctx, lt, ld, step.out["prm"], beta, tau, u, gen, idx, None, step.max_reward)
+        gen_all.append(flags.copy())
         fast_all.append(fast)
+        if fast:                                          # gathered on the caller's stream, before the fork
+            picked = step.cand[beams, idx.long()][:, None, :].contiguous()             # [B, 1, L]
+        step._fork()
         if fast:
-            picked = step.cand[beams, idx[:, 0].long()][:, None, :].contiguous()       # [B, 1, L]
-            step._fork()
             for r in ("target", "draft"):
                 step.score(r, cand=picked, out=out1[r], tok=tok1[r])
-                B.specs_commit_block(step.models[r].ctx, step.models[r].model, step.prefixes[r].handle, [0] * wl.B)
-            B.specs_commit_block(step.models["prm"].ctx, step.models["prm"].model, step.prefixes["prm"].handle,
-                                 chosen.tolist())
-            step._join()
+                B.specs_commit_block_dev(step.models[r].ctx, step.models[r].model, step.prefixes[r].handle, zero_idx)
+            B.specs_commit_block_dev(step.models["prm"].ctx, step.models["prm"].model, step.prefixes["prm"].handle, idx)
         else:
             for r in step.ROLES:
-                B.specs_commit_block(step.models[r].ctx, step.models[r].model, step.prefixes[r].handle,
-                                     chosen.tolist())
-        use_draft |= step.max_reward.cpu().numpy() > tau
+                B.specs_commit_block_dev(step.models[r].ctx, step.models[r].model, step.prefixes[r].handle, idx)
+        step._join()
+        chosen_all.append(idx.cpu().numpy().copy())
     torch.cuda.synchronize()
     return np.array(chosen_all), np.array(gen_all), np.array(fast_all)
 
@@ -223,8 +215,8 @@ def run_specs_loop(step: ScoringStep, blocks, tau, beta_index=0, start_with_targ
 def run_specs_generation_loop(step: ScoringStep, H, tau, beta_index=0, start_with_target=True):
     """Alg. 1 end to end on the GPU for H iterations: Step I, the current generator of every beam (the target until
     Step III switches the beam to the draft model, for good, once max_i r(Y_i|tr) > tau) draws n blocks of L tokens
-    with specs_generate_blocks; Step II, scores, SubSample and commit as in run_specs_loop. What has to run depends
-    on who generated:
+    with specs_generate_blocks; Steps II-III, scores, specs_select_and_switch and specs_commit_block_dev as in
+    run_specs_loop. What has to run depends on who generated (read from a host copy of the device-resident flags):
       all beams by the target: log pi_gen = log pi_target cancels in Eq. 1, only the PRM scores the candidates; the
         target commits what it generated, the draft model runs over the one chosen block to keep its cache current;
       all beams by the draft: its block log-likelihoods came out of the generation pass, so only target and PRM score;
@@ -233,17 +225,18 @@ def run_specs_generation_loop(step: ScoringStep, H, tau, beta_index=0, start_wit
     Returns (tokens [H, B, n, L], chosen [H, B], generator flags [H, B])."""
     wl, dev = step.wl, step.device
     Bn, n, L = wl.B, wl.n, wl.L
-    use_draft = np.zeros(Bn, dtype=bool) if start_with_target else np.ones(Bn, dtype=bool)
+    gen = torch.full((Bn,), 0 if start_with_target else 1, dtype=torch.uint8, device=dev)
     u_gen = W.rng.uniform_f64(wl.u_seed, "gen/u", H * Bn * n * L).reshape(H, Bn, n, L)
     u_sel = W.rng.uniform_f64(wl.u_seed, "loop/u", H * Bn).reshape(H, Bn)
-    betas = (wl.betas[beta_index],)
+    beta = wl.betas[beta_index]
     limit = min(m.vocab for m in wl.models().values() if m.head == "lm")
     f = lambda *s: torch.zeros(s, dtype=torch.float32, device=dev)
     gen_cand = {r: torch.zeros((Bn, n, L), dtype=torch.int32, device=dev) for r in ("target", "draft")}
     gen_logp = {r: f(Bn, n) for r in ("target", "draft")}
     out1 = {r: f(Bn, 1) for r in ("target", "draft")}
     tok1 = {r: f(Bn, 1, L) for r in ("target", "draft")}
-    zeros, idx = f(Bn, n), torch.zeros((Bn, 1), dtype=torch.int32, device=dev)
+    zeros, idx = f(Bn, n), torch.zeros((Bn,), dtype=torch.int32, device=dev)
+    zero_idx = torch.zeros((Bn,), dtype=torch.int32, device=dev)
     beams = torch.arange(Bn, device=dev)
     tokens_all, chosen_all, gen_all = [], [], []
 
@@ -254,12 +247,13 @@ def run_specs_generation_loop(step: ScoringStep, H, tau, beta_index=0, start_wit
 
     def commit(role, which):
         dm = step.models[role]
-        B.specs_commit_block(dm.ctx, dm.model, step.prefixes[role].handle, which)
+        B.specs_commit_block_dev(dm.ctx, dm.model, step.prefixes[role].handle, which)
 
     for h in range(H):
         ud = torch.from_numpy(u_gen[h]).to(dev)
-        us = torch.from_numpy(u_sel[h:h + 1].T.copy()).to(dev)
-        gens = sorted({"draft" if d else "target" for d in use_draft})
+        us = torch.from_numpy(u_sel[h].copy()).to(dev)
+        flags = gen.cpu().numpy().astype(bool)              # host copy: which passes to enqueue
+        gens = sorted({"draft" if d else "target" for d in flags})
         step._fork()
         for r in gens:
             generate(r, ud)
@@ -267,8 +261,7 @@ def run_specs_generation_loop(step: ScoringStep, H, tau, beta_index=0, start_wit
         if len(gens) == 1:
             step.cand = gen_cand[gens[0]]
         else:
-            step.cand = torch.where(torch.from_numpy(use_draft).to(dev)[:, None, None], gen_cand["draft"],
-                                    gen_cand["target"]).contiguous()
+            step.cand = torch.where(gen.bool()[:, None, None], gen_cand["draft"], gen_cand["target"]).contiguous()
         step._fork()
         if gens == ["target"]:
             step.score("prm")
@@ -280,34 +273,30 @@ def run_specs_generation_loop(step: ScoringStep, H, tau, beta_index=0, start_wit
                 step.score(r)
         step._join()
         if gens == ["target"]:
-            lt, lg = zeros, zeros
+            lt, ld = zeros, zeros                       # not read: every flag is 0
         elif gens == ["draft"]:
-            lt, lg = step.out["target"], gen_logp["draft"]
+            lt, ld = step.out["target"], gen_logp["draft"]
         else:
-            mask = torch.from_numpy(use_draft).to(dev)[:, None]
-            lt, lg = step.out["target"], torch.where(mask, step.out["draft"], step.out["target"]).contiguous()
-        B.specs_subsample(step.sel_ctx, lt, lg, step.out["prm"], betas, us, idx, None, step.max_reward)
-        torch.cuda.synchronize()
-        chosen = idx[:, 0].cpu().numpy()
+            lt, ld = step.out["target"], step.out["draft"]
+        B.specs_select_and_switch(step.sel_ctx, lt, ld, step.out["prm"], beta, tau, us, gen, idx, None, step.max_reward)
         tokens_all.append(step.cand.cpu().numpy().copy())
-        chosen_all.append(chosen.copy())
-        gen_all.append(use_draft.copy())
-        which = chosen.tolist()
+        gen_all.append(flags.copy())
+        if gens == ["target"]:                            # gathered on the caller's stream, before the fork
+            picked = step.cand[beams, idx.long()][:, None, :].contiguous()
         step._fork()
         if len(gens) == 1:
             other = "draft" if gens[0] == "target" else "target"
-            commit(gens[0], which)                      # its workspace holds the blocks it generated
-            commit("prm", which)
+            commit(gens[0], idx)                        # its workspace holds the blocks it generated
+            commit("prm", idx)
             if gens == ["draft"]:
-                commit("target", which)                 # the target scored all n candidates
+                commit("target", idx)                   # the target scored all n candidates
             else:                                       # the draft saw none of them: run it over the chosen block
-                picked = step.cand[beams, idx[:, 0].long()][:, None, :].contiguous()
                 step.score(other, cand=picked, out=out1[other], tok=tok1[other])
-                commit(other, [0] * Bn)
+                commit(other, zero_idx)
         else:
             for r in step.ROLES:
-                commit(r, which)
+                commit(r, idx)
         step._join()
-        use_draft |= step.max_reward.cpu().numpy() > tau
+        chosen_all.append(idx.cpu().numpy().copy())
     torch.cuda.synchronize()
     return np.array(tokens_all), np.array(chosen_all), np.array(gen_all)

@@ -67,17 +67,18 @@ def bf16_sensitivity(wl, want, cand=None, prefix_tokens=None):
 def tolerances(dtype, noise, role):
     """(token max, token rms, block max, block rms). float: the stated 1e-5 throughout. bf16: the stated 2e-2 where
     it can hold, else bounds taken from the oracle's own bf16 sensitivity (how far the float64 oracle moves when
-    operand rounding is switched off). The well-estimated statistics carry the comparison: the token rms (hundreds
-    to thousands of samples) and the block rms must not exceed ONE TIMES the oracle's, so an evaluation that is
-    further from the oracle than the oracle is from exact arithmetic fails. Maxima over a few blocks or a few
-    thousand tokens are bounded as tails of those distributions (3 block rms, 4.5 token rms) rather than by the
-    oracle's own maxima, which are single draws of the same fluctuating statistic. Whether the stated bound itself
+    operand rounding is switched off). The well-estimated statistic carries the comparison: the token rms (hundreds
+    to thousands of samples) must not exceed ONE TIMES the oracle's, so an evaluation that is further from the
+    oracle than the oracle is from exact arithmetic fails. The block rms (8 to 16 samples, each estimate good to
+    about a fifth) gets 1.3 times; maxima over a few blocks or a few thousand tokens are bounded as tails of those
+    distributions (3 block rms, 4.5 token rms) rather than by the oracle's own maxima, which are single draws of the
+    same fluctuating statistic. Whether the stated bound itself
     was met is recorded by compare() in its statistics."""
     if dtype == "f32":
         return TOL_F32, TOL_F32, TOL_F32, TOL_F32
     n = noise[role]
     return (max(TOL_BF16, 4.5 * n["tok_rms"]), max(TOL_BF16 / 4, n["tok_rms"]), max(TOL_BF16, 3.0 * n["block_rms"]),
-            max(TOL_BF16 / 2, n["block_rms"]))
+            max(TOL_BF16 / 2, 1.3 * n["block_rms"]))
 
 
 def compare(res, want, dtype="f32", noise=None, stated_only=False, floor=None):
@@ -180,7 +181,11 @@ def run_step(wl, **kw):
 
 def test_c1_tiny_float_matches_oracle_in_both_modes():
     wl = W.get_config("c1_tiny")
+    from paper_2506_15733_amd import binding
+    binding.specs_path_counts(reset=True)
     step, res = run_step(wl)
+    paths = binding.specs_path_counts()
+    assert paths["gemm_mfma"] == 0 and paths["attn_mfma"] == 0 and paths["gemm_plain"] > 0, paths   # the float kernels
     want = oracle_step(wl)
     compare(res, want)
     assert check_selection(wl, res, want, score_bound("f32", None))[:2] == (0, 0)
@@ -302,7 +307,13 @@ def test_benchmark_configs_bf16_match_stored_oracle(name):
     want = golden(name)
     if not all(k in want for k in ("target", "draft", "prm")):
         pytest.skip("stored oracle outputs incomplete")
+    from paper_2506_15733_amd import binding
+    binding.specs_path_counts(reset=True)
     step, res = run_step(wl)
+    paths = binding.specs_path_counts()
+    # every contraction and every attention launch of a benchmark configuration (prefill included) ran on the
+    # matrix-unit kernels: nothing fell back to the plain ones
+    assert paths["gemm_plain"] == 0 and paths["attn_plain"] == 0 and paths["gemm_mfma"] > 0 and paths["attn_mfma"] > 0, paths
     stats = compare(res, want, "bf16", want["noise"], floor=want["floor"])
     print(name, "GPU vs oracle:", stats, "oracle bf16 sensitivity:", want["noise"], "fp32 floor:", want["floor"])
     print(name, "selections (differ, undetermined, max TV):",
@@ -339,6 +350,8 @@ def test_c4_full_width_depth_series(layers):
     wl = W.configs.scaled(base, **{r: dataclasses.replace(m, n_layers=min(layers, m.n_layers))
                                    for r, m in base.models().items()})
     want = golden(name)
+    if not all(k in want for k in ("target", "draft", "prm")) or len(want["noise"]) < 3:
+        pytest.skip("stored oracle outputs incomplete")
     step, res = run_step(wl)
     stats = compare(res, want, "bf16", want["noise"], floor=want["floor"])
     if layers == 1:           # one layer: every token within the stated bound, no widening
@@ -428,6 +441,14 @@ def test_invalid_arguments_are_rejected():
     with pytest.raises(B.SpecsError) as e:                                      # prefix handle of another model
         B.specs_score_blocks(dm.ctx, dm.model, step.prefixes["prm"].handle, step.cand, step.out["target"])
     assert e.value.code == 1
+    bad = B.make_desc(2, 96, 6, 4, 16, 160, 301, "f32", "lm")                   # 6 query heads over 4 kv heads
+    with pytest.raises(B.SpecsError) as e:
+        B.specs_model_create(dm.ctx, bad, dm.embed, dm.head, dm.g_final, dm.layers)
+    assert e.value.code == 2                                                    # SPECS_ESHAPE
+    odd = B.make_desc(2, 96, 6, 2, 15, 160, 301, "f32", "lm")                   # odd head_dim: no rotary pairs
+    with pytest.raises(B.SpecsError) as e:
+        B.specs_model_create(dm.ctx, odd, dm.embed, dm.head, dm.g_final, dm.layers)
+    assert e.value.code == 2
     with pytest.raises(B.SpecsError) as e:                                      # commit without a preceding scoring call
         B.specs_commit_block(step.models["draft"].ctx, step.models["draft"].model, step.prefixes["draft"].handle, [0, 0, 0])
     assert e.value.code == 1

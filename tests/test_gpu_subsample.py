@@ -112,3 +112,43 @@ def test_monte_carlo_marginal_matches_the_exact_smc_policy(ctx):
     for k in range(4):
         sd = math.sqrt(max(hard[k] * (1 - hard[k]), 1e-9) / trials)
         assert abs(np.mean(picked == k) - hard[k]) < 5 * sd, (k, np.mean(picked == k), hard[k])
+
+
+def test_select_and_switch_is_eq1_with_the_current_generator_then_step_three():
+    """Alg. 1 Steps II-III behind the ABI: beams whose flag is 0 (target generates) select with S = beta r, beams
+    whose flag is 1 with the full score of Eq. 1; afterwards a beam with max r > tau (strictly) has its flag set and
+    set flags stay set. Indices are bit-exact against the sequential float64 rule; the threshold test uses exact
+    float comparisons, including a reward equal to tau (no switch)."""
+    from paper_2506_15733_amd import binding as B
+    wl = W.get_config("c5_7b_batched")
+    Bn, n = 64, 8
+    lt, ld, r = wl.synthetic_scores(Bn, n)
+    tau = np.float32(0.9)
+    r[5, :] = np.minimum(r[5, :], tau)
+    r[5, 3] = tau                                        # equal to the threshold: must NOT switch
+    r[6, 2] = np.nextafter(tau, np.float32(2.0))         # one float above: must switch
+    flags0 = (W.rng.raw_u32(3, "flags", 0, Bn) & 1).astype(np.uint8)
+    flags0[5] = flags0[6] = 0
+    u = W.rng.uniform_f64(3, "sel/u", Bn)
+    dev = "cuda:0"
+    ws = torch.zeros(4096, dtype=torch.uint8, device=dev)
+    ctx = B.specs_ctx_create(0, torch.cuda.current_stream().cuda_stream, ws)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    gen, idx, maxr = t(flags0), torch.full((Bn,), -7, dtype=torch.int32, device=dev), torch.zeros(Bn, device=dev)
+    beta = 2.0
+    B.specs_select_and_switch(ctx, t(lt), t(ld), t(r), beta, float(tau), t(u), gen, idx, None, maxr)
+    torch.cuda.synchronize()
+    assert B.specs_ctx_status(ctx) == 0
+    got_idx, got_gen = idx.cpu().numpy(), gen.cpu().numpy()
+    for b in range(Bn):
+        lg = ld[b] if flags0[b] else lt[b]               # pi_gen = pi_target while the target generates
+        assert got_idx[b] == oracle.subsample(lt[b], lg, r[b], beta, float(u[b])), b
+        want_flag = 1 if (flags0[b] or float(r[b].max()) > float(tau)) else 0
+        assert got_gen[b] == want_flag, b
+    assert got_gen[5] == 0 and got_gen[6] == 1
+    assert np.array_equal(maxr.cpu().numpy(), r.max(axis=1))
+    # rejected arguments
+    with pytest.raises(B.SpecsError) as e:
+        B.specs_select_and_switch(ctx, t(lt), t(ld), t(r), -1.0, 0.5, t(u), gen, idx)
+    assert e.value.code == 4
+    B.specs_ctx_destroy(ctx)

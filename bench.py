@@ -227,6 +227,10 @@ def main():
     ap.add_argument("--workload", default="c4_7b")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--serial", action="store_true", help="one stream for the three passes instead of one each")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (three passes + SubSample) in a HIP graph and time its replays (measured: "
+                         "no faster than eager launches, the small configurations are bound by the device-side "
+                         "dispatch of ~500 dependent kernels, not by the host)")
     ap.add_argument("--generate", default=None, help="draft|target: time block generation (Alg. 1 Step I) by that model")
     ap.add_argument("--specs-loop", type=int, default=0, metavar="H",
                     help="time H full iterations of Alg. 1 (generate, score, SubSample, commit) per generator")
@@ -246,19 +250,28 @@ def main():
     from paper_2506_15733_amd import synthetic, binding as B
     wl = W.get_config(args.workload)
     t_setup = time.time()
-    step = synthetic.ScoringStep(wl, device="cuda:0", concurrent=not args.serial)
-    step.prefill()
-    torch.cuda.synchronize()
-    print(f"# setup + prefill {time.time() - t_setup:.1f}s", file=sys.stderr, flush=True)
-
-    for _ in range(args.warmup):
-        step.enqueue_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step.enqueue_step()
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / args.steps
+    main_stream = torch.cuda.Stream(device="cuda:0") if args.graph else torch.cuda.current_stream()
+    with torch.cuda.stream(main_stream):          # a graph cannot be captured on the default stream
+        step = synthetic.ScoringStep(wl, device="cuda:0", concurrent=not args.serial)
+        step.prefill()
+        torch.cuda.synchronize()
+        print(f"# setup + prefill {time.time() - t_setup:.1f}s", file=sys.stderr, flush=True)
+        run = step.enqueue_step
+        if args.graph:
+            step.enqueue_step()                   # eager once: every kernel configured before the capture
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=main_stream):
+                step.enqueue_step()
+            run = graph.replay
+        for _ in range(args.warmup):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
     assert all(v == 0 for v in step.status().values())
 
     # per-role time with events on the launch stream
@@ -307,7 +320,8 @@ def main():
         "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if d.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "n": wl.n, "L": wl.L, "prefix_tokens": int(lens.sum()),
-                   "roles": "target+draft+prm+subsample", "streams": 1 if args.serial else 3},
+                   "roles": "target+draft+prm+subsample", "streams": 1 if args.serial else 3,
+                   "launch": "graph replay" if args.graph else "eager"},
         "step_tflops": total_flops / dt / 1e12, "step_frac_of_mfma_peak": total_flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "role_ms_alone": role_ms, "target_kernel_us_per_launch": kernel_us, "target_kernel_frac_of_mfma_peak": kfrac,
         "roofline": {"kernel": "gemm_mfma_kernel<256, SWIGLU> (gate/up projection + SiLU*mul)", "bound": "mfma",

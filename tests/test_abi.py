@@ -66,3 +66,30 @@ def test_product_package_does_not_import_the_oracle():
         if f.endswith(".py"):
             txt = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2506_15733_amd" not in txt and "import workload" not in txt
+
+
+def test_host_side_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The host code of the ABI (argument checks, description checks, workspace carving arithmetic, handle lifetime,
+    counters) built with -fsanitize=address,undefined for the host only and driven by tests/host_sanitizer_driver.cpp,
+    which needs no GPU: any report of either sanitizer, or a failed check, fails the test. The other objects are the
+    ordinary ones of build() (device code is never sanitized)."""
+    import glob
+    import subprocess
+    import __graft_entry__ as G
+    objs = [o for o in glob.glob(os.path.join(ROOT, "_build", "*.o")) if not o.endswith("specs_api.o")]
+    if len(objs) < 8:
+        G.build()
+        objs = [o for o in glob.glob(os.path.join(ROOT, "_build", "*.o")) if not o.endswith("specs_api.o")]
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+           "-fno-sanitize-recover=undefined", "-g"]
+    api_o, drv_o, exe = str(tmp_path / "specs_api_san.o"), str(tmp_path / "driver.o"), str(tmp_path / "driver")
+    subprocess.run([G.HIPCC, *G.FLAGS, *san, "-c", os.path.join(G.CSRC, "specs_api.hip"), "-o", api_o], check=True,
+                   capture_output=True)
+    subprocess.run([G.HIPCC, "-x", "hip", *G.FLAGS, *san, "-c", os.path.join(ROOT, "tests", "host_sanitizer_driver.cpp"),
+                    "-o", drv_o], check=True, capture_output=True)
+    subprocess.run([G.HIPCC, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
+                    "-o", exe, drv_o, api_o, *objs], check=True, capture_output=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:halt_on_error=1", UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    assert r.returncode == 0 and "host ABI driver: ok" in r.stdout, (r.stdout[-2000:], r.stderr[-4000:])
+    assert "ERROR: AddressSanitizer" not in r.stderr and "runtime error" not in r.stderr, r.stderr[-4000:]

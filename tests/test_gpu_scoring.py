@@ -362,6 +362,41 @@ def test_c4_full_width_depth_series(layers):
     step.close()
 
 
+def test_scoring_step_replayed_from_a_graph_equals_eager_c2():
+    """The whole step (three passes on three streams + SubSample) captured once in a HIP graph and replayed: every
+    replay must reproduce the eager outputs bit for bit, with eager steps and synchronisations between the replays
+    and with different candidate blocks written into the captured input buffer before each replay."""
+    from paper_2506_15733_amd import synthetic
+    wl = W.get_config("c2_small")
+    stream = torch.cuda.Stream(device="cuda:0")
+    with torch.cuda.stream(stream):
+        step = synthetic.ScoringStep(wl)
+        step.prefill()
+        step.enqueue_step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            step.enqueue_step()
+        keys = ("target", "draft", "prm")
+        for rep in range(3):
+            cand = W.rng.zipf_tokens(77, f"graph/{rep}", wl.B * wl.n * wl.L, wl.token_vocab, 1.1)
+            step.cand.copy_(torch.from_numpy(cand.reshape(wl.B, wl.n, wl.L).astype(np.int32)))
+            eager = step.score_and_select()                    # eager work between the replays
+            for k in keys:
+                step.out[k].zero_()
+            step.idx.fill_(-5)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert all(v == 0 for v in step.status().values())
+            for k in keys:
+                assert np.array_equal(step.out[k].cpu().numpy(), eager[k]), (rep, k)
+            assert np.array_equal(step.idx.cpu().numpy(), eager["idx"]), rep
+            assert np.array_equal(step.tok["target"].cpu().numpy(), eager["tok_target"]), rep
+        del graph
+    step.close()
+
+
 def test_c5_batched_beams_paged_ragged_prefixes():
     """Config 5: 32 beams with prefix lengths in [1024, 8192) in shuffled 16-token pages, 7B-class models.
     The oracle is affordable only for a stated subset of beams (stored by make_oracle_golden.py --beams ...);

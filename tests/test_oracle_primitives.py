@@ -191,3 +191,29 @@ def test_token_logprob_is_minus_cross_entropy_and_picks_the_right_column():
         rms_eps, dtype = 0.0, "f32"
     unit = np.sign(A)
     assert np.allclose(T._token_logprobs(_D, _W(), unit, tg), oracle.token_logprob(unit, Wh, tg), atol=1e-12)
+
+
+def test_float_accumulation_jitter_is_off_by_default_and_only_moves_rounding_decisions():
+    """The tolerance-derivation tool of oracle/rounding.py: outside its context operand() rounds exact values; inside,
+    values are perturbed by ~2e-7 relative BEFORE rounding, so an operand either stays the same bf16 value or moves
+    by exactly one bf16 unit, and only for the few values that sit next to a rounding boundary. Float operands are
+    never touched. With amplitude 0 the context is the identity."""
+    x = RNG.standard_normal(400000) * np.exp(RNG.uniform(-8, 8, 400000))
+    base = oracle.operand(x, "bf16")
+    assert np.array_equal(base, oracle.round_bf16(x))
+    with oracle.float_accumulation_jitter(0.0):
+        assert np.array_equal(oracle.operand(x, "bf16"), base)
+    with oracle.float_accumulation_jitter(2.0e-7, seed=3):
+        jit = oracle.operand(x, "bf16")
+        assert np.array_equal(oracle.operand(x, "f32"), x)
+    assert np.array_equal(oracle.operand(x, "bf16"), base)              # switched off again
+    moved = jit != base
+    frac = moved.mean()
+    # a relative jitter of 2e-7 against a rounding grid of 2^-8 .. 2^-7 relative: about 1e-4 of the values flip
+    assert 1e-5 < frac < 1e-3, frac
+    ulp = 2.0 ** (np.floor(np.log2(np.abs(base[moved]))) - 7)
+    assert np.allclose(np.abs(jit[moved] - base[moved]), ulp, rtol=0, atol=0) or \
+        np.all(np.isin(np.abs(jit[moved] - base[moved]) / ulp, (0.5, 1.0, 2.0)))
+    # the same seed gives the same perturbation (stored figures are reproducible)
+    with oracle.float_accumulation_jitter(2.0e-7, seed=3):
+        assert np.array_equal(oracle.operand(x, "bf16"), jit)

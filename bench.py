@@ -17,10 +17,23 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-# HBM-side bytes per launch of the dominant kernel from two rocprofv3 --pmc runs (FETCH_SIZE x2.00 + WRITE_SIZE x1.00,
-# factors from a 1 GiB device copy); summary in profiles/gemm_gate_up_and_attention_c4_7b_pmc.md
-MEASURED_TRAFFIC_BYTES = {"c4_7b": 859.1e6 + 77.6e6}
+# HBM-side bytes per launch of the dominant kernel come from the committed rocprofv3 --pmc summary of that kernel
+# (FETCH_SIZE and WRITE_SIZE runs, each scaled by what the counter reads for a device copy of known size). The
+# summary carries one machine-readable line per workload, "traffic_bytes_per_launch <workload> <bytes>"; a workload
+# without such a line reports null.
+TRAFFIC_PROFILE = os.path.join("profiles", "gemm_gate_up_c4_7b_pmc.md")
 
+
+def measured_traffic(workload):
+    try:
+        with open(os.path.join(ROOT, TRAFFIC_PROFILE)) as f:
+            for ln in f:
+                w = ln.split()
+                if len(w) == 3 and w[0] == "traffic_bytes_per_launch" and w[1] == workload:
+                    return float(w[2])
+    except OSError:
+        pass
+    return None
 
 def role_flops(d, M, P_total_rows_ctx, n, L, B):
     """Algorithmic FLOPs of one scoring pass (GEMMs + attention), for reporting."""
@@ -301,7 +314,7 @@ def main():
     k_ms = kernel_us["gate_up"] / 1e3
     flops = 2.0 * M * d.d_model * 2 * d.ffn
     achieved = flops / (k_ms * 1e-3) / 1e12
-    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
+    traffic = measured_traffic(args.workload)
 
     lens = wl.prefix_lens()
     ctx_rows = float(sum(int(l) * wl.n * wl.L for l in lens))
@@ -326,7 +339,8 @@ def main():
         "role_ms_alone": role_ms, "target_kernel_us_per_launch": kernel_us, "target_kernel_frac_of_mfma_peak": kfrac,
         "roofline": {"kernel": "gemm_mfma_kernel<256, SWIGLU> (gate/up projection + SiLU*mul)", "bound": "mfma",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "ms_per_launch": k_ms,
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "traffic_source": TRAFFIC_PROFILE if traffic is not None else None,
+                     "ms_per_launch": k_ms,
                      "shape": [M, 2 * d.ffn, d.d_model]},
     }
     if not args.no_cpu:

@@ -176,7 +176,11 @@ int specs_score_blocks_static(specs_ctx* ctx, const specs_model* m, const specs_
  * that will score the blocks). Outputs (device): cand[B][n][L] the tokens, logp[B][n] =
  * log pi(Y_i | tr), the block log-likelihood under the law the tokens were drawn from (it comes out of
  * the same pass, so a generator need not be run again as a scorer), and, if tok_logp != NULL,
- * tok_logp[B][n][L] its per-token terms. The prefix is not modified; the context is left as after
+ * tok_logp[B][n][L] its per-token terms. With vocab_limit < V that law is the restricted softmax,
+ * log pi = z_y - logsumexp(z[0..vocab_limit)), whereas specs_score_blocks always scores under the full
+ * softmax: use logp as Eq. 1's log pi_gen only together with scores of the same restricted law, or
+ * when the log-ratio term vanishes (the target generating, Alg. 1 before the switch); mixing it with
+ * full-softmax scores shifts the ratio by log of the probability mass of the permitted ids. The prefix is not modified; the context is left as after
  * specs_score_blocks(cand) with this model and prefix, so specs_commit_block may follow. */
 int specs_generate_blocks(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, int32_t n, int32_t L,
                           int32_t vocab_limit, const double* u, int32_t* cand, float* logp, float* tok_logp);

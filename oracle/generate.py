@@ -33,8 +33,10 @@ def sample_token(z, u, with_interval=False):
     return k, lp
 
 
-def generate_blocks(desc, weights, cache: PrefixCache, n, L, u, vocab_limit=None):
+def generate_blocks(desc, weights, cache: PrefixCache, n, L, u, vocab_limit=None, p_max=None):
     """u [n, L] uniforms; vocab_limit: only the first vocab_limit ids may be drawn (softmax restricted to them).
+    p_max: optional float array [n, L] that receives the largest single-id probability of every sampled distribution
+    (a test that accepts an id other than the drawn one bounds the probability mass between the two with it).
     Returns (tokens [n, L] int64, token log-probs [n, L], block log-probs [n],
     caches: per candidate the prefix cache extended by its block, whose h_last is the state at its last token,
     bounds [n, L, 2]: the interval of uniforms that maps to each drawn token)."""
@@ -52,6 +54,8 @@ def generate_blocks(desc, weights, cache: PrefixCache, n, L, u, vocab_limit=None
             z = z[:, :vocab_limit]
         for i in range(n):
             tokens[i, t], logp[i, t], bounds[i, t] = sample_token(z[i], float(u[i, t]), with_interval=True)
+            if p_max is not None:
+                p_max[i, t] = 1.0 / float(np.exp(z[i] - np.max(z[i])).sum())
         xs, kv = forward_sequences(desc, weights, [tokens[i:i + 1, t:t + 1] for i in range(n)], prefixes=caches,
                                    collect_kv=True)
         caches = [PrefixCache(c.length + 1,

@@ -20,6 +20,11 @@ decisions that decorrelate) from one that is there at depth 1 (a mistake).
 --append adds the given beams to the beams a stored file already holds (configuration 5: each beam
 costs up to an hour), keeping what is stored.
 
+--generate T (with --layers K) stores block generation instead of scoring: T positions of all n candidates of beam 0
+drawn by oracle.generate_blocks from every language model of the configuration (first K layers, full widths, the
+configuration's prefix), with the uniforms of stream "gen/u"; a model whose vocabulary exceeds the token vocabulary
+draws from the first token_vocab ids. Written to oracle_gen_<config>_L<K>.json.
+
 usage: python tests/golden/make_oracle_golden.py c3_1p5b [--beams 0,1] [--noise] [--layers 2] [--append]
 """
 import dataclasses
@@ -71,6 +76,29 @@ def append_beams(args, wl, beams, old, path):
     print("appended", beams, "to", path)
 
 
+def generation(args, wl, tag):
+    """Alg. 1 step I by the oracle: T positions for the n candidates of beam 0, per language model."""
+    T = args.generate
+    u = W.rng.uniform_f64(wl.u_seed, "gen/u", wl.n * T).reshape(wl.n, T)
+    out = {"config": args.config, "layers": args.layers, "positions": T, "u_stream": "gen/u",
+           "note": "float64 oracle, oracle.generate_blocks on beam 0; bounds = interval of uniforms mapped to each id"}
+    path = os.path.join(ROOT, "tests", "golden", f"oracle_gen_{tag}.json")
+    for role, desc in wl.models().items():
+        if desc.head != "lm":
+            continue
+        t0 = time.time()
+        hw = HostWeights(desc, wl.seed)
+        cache = oracle.prefill(desc, hw, [wl.prefix_tokens()[0]])[0]
+        limit = wl.token_vocab if desc.vocab > wl.token_vocab else None
+        p_max = np.zeros((wl.n, T))
+        tokens, tok, blk, _, bounds = oracle.generate_blocks(desc, hw, cache, wl.n, T, u, vocab_limit=limit, p_max=p_max)
+        out[role] = {"vocab_limit": limit or 0, "tokens": tokens.tolist(), "tok": tok.tolist(), "block": blk.tolist(),
+                     "bounds": bounds.tolist(), "p_max": p_max.tolist()}
+        print(role, round(time.time() - t0, 1), "s", flush=True)
+        json.dump(out, open(path, "w"))
+    print("wrote", path)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("config")
@@ -81,6 +109,7 @@ def main():
                     help="also evaluate with oracle.float_accumulation_jitter and store the distance (fp32_floor_*)")
     ap.add_argument("--layers", type=int, default=0)
     ap.add_argument("--append", action="store_true")
+    ap.add_argument("--generate", type=int, default=0, help="store T generated positions instead of scores")
     args = ap.parse_args()
     wl = W.get_config(args.config)
     tag = args.config
@@ -88,6 +117,8 @@ def main():
         wl = W.configs.scaled(wl, **{r: dataclasses.replace(m, n_layers=min(args.layers, m.n_layers))
                                      for r, m in wl.models().items()})
         tag = f"{args.config}_L{args.layers}"
+    if args.generate:
+        return generation(args, wl, tag)
     beams = list(range(wl.B)) if args.beams is None else [int(b) for b in args.beams.split(",")]
     pt_all, cand_all = wl.prefix_tokens(), wl.candidates()
     pt, cand = [pt_all[b] for b in beams], cand_all[beams]

@@ -41,8 +41,14 @@ def gpu_generate(step, role, u, vocab_limit=0):
     return cand.cpu().numpy(), logp.cpu().numpy(), tok.cpu().numpy()
 
 
-def compare_generation(cand, tok, logp, o_tokens, o_tok, o_blk, o_bounds, u, tol_lp, eta):
-    """Returns the fraction of token positions compared (those before a candidate's first differing id)."""
+def compare_generation(cand, tok, logp, o_tokens, o_tok, o_blk, o_bounds, u, tol_lp, eta, p_max=None):
+    """Returns the fraction of token positions compared (those before a candidate's first differing id).
+    A differing id must be one the tolerance allows: logits within delta move every value of the distribution
+    function by a factor within exp(+-2 delta), so the uniform must lie within eta = exp(2 delta) - 1 of the
+    oracle's interval of the id the GPU drew. Without p_max (small vocabularies, where an id's interval is wide)
+    that id must be the oracle's neighbour and u within eta of the boundary between them; with p_max (the oracle's
+    largest single-id probability at that position) the mass between the two ids is at most |id difference| * p_max,
+    and that plus the distance of u from the oracle's interval must stay within eta."""
     n, L = o_tokens.shape
     compared = 0
     for i in range(n):
@@ -56,7 +62,11 @@ def compare_generation(cand, tok, logp, o_tokens, o_tok, o_blk, o_bounds, u, tol
         lo, hi = o_bounds[i, first]
         near = min(u[i, first] - lo, hi - u[i, first])
         assert near <= eta, (i, first, near, int(cand[i, first]), int(o_tokens[i, first]))
-        assert abs(int(cand[i, first]) - int(o_tokens[i, first])) == 1, (i, first)
+        gap = abs(int(cand[i, first]) - int(o_tokens[i, first]))
+        if p_max is None:
+            assert gap == 1, (i, first)
+        else:
+            assert near + gap * p_max[i, first] <= eta, (i, first, near, gap, p_max[i, first])
     return compared / (n * L)
 
 
@@ -269,6 +279,62 @@ def test_generation_equals_scoring_at_config_4_size():
     assert np.sqrt((dt ** 2).mean()) < max(5e-3, noise["tok_rms"])
     assert dt.max() < max(2e-2, 4.5 * noise["tok_rms"])
     assert db.max() < max(2e-2, 3.0 * noise["block_rms"])
+    step.close()
+
+
+def test_full_width_one_layer_generators_match_the_stored_oracle():
+    """Both language models of config 4 at their full widths (7B: d 3584, F 18944, V 152064; 1.5B: d 1536, F 8960)
+    with their first layer only, on the 4096-token prefix, generating 8 positions for 16 candidates: the launches
+    generation uses at the benchmark size (few-row weight-streaming GEMMs, one-position attention over the paged
+    prefix merged with the block's own keys, the sampler over the full vocabulary) against oracle.generate_blocks,
+    whose ids, log-probabilities and uniform intervals make_oracle_golden.py --generate stored. The 7B model's
+    vocabulary exceeds the token vocabulary, so it draws from the restricted law (vocab_limit). Ids must equal the
+    oracle's up to a candidate's first position where its uniform lies within eta of an interval boundary; token
+    log-probabilities before that within the stated 2e-2."""
+    import json, os
+    from paper_2506_15733_amd import synthetic
+    path = os.path.join(os.path.dirname(__file__), "golden", "oracle_gen_c4_7b_L1.json")
+    if not os.path.exists(path):
+        pytest.skip("tests/golden/oracle_gen_c4_7b_L1.json not generated")
+    want = json.load(open(path))
+    T = want["positions"]
+    base = W.get_config("c4_7b")
+    wl = W.configs.scaled(base, L=T, **{r: dataclasses.replace(m, n_layers=want["layers"])
+                                         for r, m in base.models().items()})
+    assert np.array_equal(wl.prefix_tokens()[0], base.prefix_tokens()[0])
+    step = synthetic.ScoringStep(wl)
+    step.prefill()
+    u = W.rng.uniform_f64(wl.u_seed, want["u_stream"], wl.n * T).reshape(1, wl.n, T)
+    for role in ("draft", "target"):
+        if role not in want:
+            pytest.skip(f"stored oracle generation lacks {role}")
+        o = want[role]
+        cand, logp, tok = gpu_generate(step, role, u, vocab_limit=o["vocab_limit"])
+        frac = compare_generation(cand[0], tok[0], logp[0], np.asarray(o["tokens"]), np.asarray(o["tok"]),
+                                  np.asarray(o["block"]), np.asarray(o["bounds"]), u[0], 2e-2, 4e-2,
+                                  p_max=np.asarray(o["p_max"]))
+        same = float((cand[0] == np.asarray(o["tokens"])).mean())
+        print(role, "full-width generation: fraction of positions compared", frac, "ids equal to the oracle's", same)
+        # A distribution over 152k ids that is nearly flat gives an id an interval of about 1e-5 of the uniform's
+        # range, while relative errors of 5e-3 in the single probabilities (bf16 operands) move the running sum at
+        # mid-vocabulary by about as much: most draws land one or two ids beside the oracle's and the histories
+        # part at once. Each such draw was checked above against the bound the tolerance implies; the arithmetic
+        # of every position is checked below on the oracle's own ids.
+        assert cand.max() < (o["vocab_limit"] or wl.models()[role].vocab)
+        gaps = np.abs(cand[0].astype(np.int64) - np.asarray(o["tokens"]))[:, 0]
+        print(role, "id distance to the oracle's at the first position:", gaps.tolist())
+        assert gaps.max() * np.asarray(o["p_max"])[:, 0].max() < 4e-2
+        # every position, also after the histories part: the block-parallel pass over the ORACLE's ids must
+        # reproduce the oracle's log-probabilities (that generation and the block-parallel pass agree on equal ids
+        # is tested separately). The 7B model scores under the full softmax while its stored values are those of
+        # the law restricted to the token vocabulary: with these weights the 128 excluded ids hold 8e-4 of the
+        # mass, a shift of 8e-4 per token, inside the tolerance.
+        step.cand = torch.from_numpy(np.asarray(o["tokens"], dtype=np.int32)[None]).to(step.device)
+        step.score(role)
+        torch.cuda.synchronize()
+        d = np.abs(step.tok[role].cpu().numpy()[0] - np.asarray(o["tok"]))
+        print(role, "scoring of the oracle's ids: max token error", float(d.max()), "rms", float(np.sqrt((d ** 2).mean())))
+        assert d.max() < 2e-2
     step.close()
 
 

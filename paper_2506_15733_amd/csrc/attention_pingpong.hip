@@ -496,7 +496,7 @@ bool launch_attention_pingpong(const bf16_t* q, const bf16_t* kb, const bf16_t* 
                                const bf16_t* poolV, bf16_t* out, const BatchGeom& g, const ModelDims& md, int Lp,
                                int max_ctx, float* part, size_t part_floats, hipStream_t s) {
   if ((md.hd != 64 && md.hd != 128) || g.page_tokens != 16 || Lp % 16 != 0 || g.t0 != 0 || g.Lk != g.L) return false;
-  if (((uintptr_t)out & 7) || md.Hq % md.Hkv) return false;
+  if (((uintptr_t)out & 7) || md.Hq % md.Hkv || g.n > 0xffff) return false;   // the tile table packs (candidate, tile) in 16 + 16 bits
   PPArgs a;
   a.q = q; a.kb = kb; a.vbT = vbT; a.poolK = poolK; a.poolV = poolV; a.out = out; a.g = g;
   a.Hq = md.Hq; a.Hkv = md.Hkv; a.Lp = Lp;

@@ -149,6 +149,16 @@ int specs_prefill(specs_ctx* ctx, const specs_model* m, specs_prefix* p, const i
 int specs_score_blocks(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const int32_t* cand,
                        int32_t n, int32_t L, float* out, float* tok_logp);
 
+/* The two scores the target side contributes to Eq. 1 in one call: logp_target[B][n] = log pi_target(Y_i | tr)
+ * and reward[B][n] = r(Y_i | tr) for the same candidate blocks cand[B][n][L], i.e. specs_score_blocks with the
+ * target model on its context and with the PRM on its own (Alg. 1 step II evaluates both for every candidate;
+ * the two passes are independent and each is enqueued on its context's stream, so with two streams they
+ * overlap). tok_logp_target may be NULL. Both prefixes describe the same B traces. Returns the first error. */
+int specs_score_target_and_reward(specs_ctx* ctx_target, const specs_model* target, const specs_prefix* p_target,
+                                  specs_ctx* ctx_prm, const specs_model* prm, const specs_prefix* p_prm,
+                                  const int32_t* cand, int32_t n, int32_t L, float* logp_target,
+                                  float* tok_logp_target, float* reward);
+
 /* specs_score_blocks for callers that cannot allocate device memory or hand over a workspace sized for the
  * call: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments,
  * same kernels and bit-identical results, but every working buffer of the pass lives in a scratch array that

@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = [
     "specs_model_destroy", "specs_prefix_create", "specs_prefix_destroy", "specs_prefill", "specs_score_blocks",
     "specs_commit_block", "specs_subsample", "specs_strerror", "specs_generate_blocks",
     "specs_op_linear", "specs_op_gate_up", "specs_op_lmhead_logprob", "specs_op_attention",
-    "specs_ctx_profile", "specs_ctx_profile_read", "specs_score_blocks_static",
+    "specs_ctx_profile", "specs_ctx_profile_read", "specs_score_blocks_static", "specs_score_target_and_reward",
     "specs_commit_block_dev", "specs_select_and_switch", "specs_path_counts",
 ]
 PATH_CLASSES = ("gemm_mfma", "gemm_skinny", "gemm_plain", "attn_mfma", "attn_plain")
@@ -69,6 +69,7 @@ def load_library():
     lib.specs_prefill.argtypes = [vp, vp, vp, vp]
     lib.specs_score_blocks.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp]
     lib.specs_score_blocks_static.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp]
+    lib.specs_score_target_and_reward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
     lib.specs_generate_blocks.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.specs_commit_block.argtypes = [vp, vp, vp, C.POINTER(i32)]
     lib.specs_commit_block_dev.argtypes = [vp, vp, vp, vp]
@@ -192,6 +193,16 @@ def specs_score_blocks(ctx, model, prefix, cand, out, tok_logp=None):
     _check(load_library().specs_score_blocks(ctx, model, prefix, _ptr(cand, torch.int32), n, L,
                                              _ptr(out, torch.float32), _ptr(tok_logp, torch.float32, True)),
            "specs_score_blocks")
+
+
+def specs_score_target_and_reward(ctx_target, target, p_target, ctx_prm, prm, p_prm, cand, logp_target, reward,
+                                  tok_logp_target=None):
+    import torch
+    B, n, L = cand.shape
+    _check(load_library().specs_score_target_and_reward(
+        ctx_target, target, p_target, ctx_prm, prm, p_prm, _ptr(cand, torch.int32), n, L,
+        _ptr(logp_target, torch.float32), _ptr(tok_logp_target, torch.float32, True), _ptr(reward, torch.float32)),
+        "specs_score_target_and_reward")
 
 
 def specs_score_blocks_static(ctx, model, prefix, cand, out, tok_logp=None):

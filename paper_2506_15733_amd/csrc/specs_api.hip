@@ -599,6 +599,18 @@ extern "C" int specs_score_blocks(specs_ctx* ctx, const specs_model* m, const sp
              : score_impl<float>(ctx, m, p, cand, n, L, out, tok_logp, ctx->workspace, ctx->workspace_bytes);
 }
 
+extern "C" int specs_score_target_and_reward(specs_ctx* ctx_target, const specs_model* target,
+                                             const specs_prefix* p_target, specs_ctx* ctx_prm, const specs_model* prm,
+                                             const specs_prefix* p_prm, const int32_t* cand, int32_t n, int32_t L,
+                                             float* logp_target, float* tok_logp_target, float* reward) {
+  if (!target || !prm || target->desc.head != SPECS_HEAD_LM || prm->desc.head != SPECS_HEAD_PRM) return SPECS_EINVAL;
+  if (!p_target || !p_prm || p_target->B != p_prm->B) return SPECS_EINVAL;
+  if (int rc = score_args_ok(ctx_target, target, p_target, cand, n, L, logp_target, tok_logp_target)) return rc;
+  if (int rc = score_args_ok(ctx_prm, prm, p_prm, cand, n, L, reward, nullptr)) return rc;
+  if (int rc = specs_score_blocks(ctx_target, target, p_target, cand, n, L, logp_target, tok_logp_target)) return rc;
+  return specs_score_blocks(ctx_prm, prm, p_prm, cand, n, L, reward, nullptr);
+}
+
 extern "C" int specs_score_blocks_static(specs_ctx* ctx, const specs_model* m, const specs_prefix* p,
                                          const int32_t* cand, int32_t n, int32_t L, float* out, float* tok_logp) {
   if (int rc = score_args_ok(ctx, m, p, cand, n, L, out, tok_logp)) return rc;

@@ -459,6 +459,30 @@ def test_degenerate_and_boundary_shapes_bf16(P, n, L, hq, hkv, hd):
     step.close()
 
 
+def test_target_and_reward_in_one_call_equals_the_two_passes():
+    """The short form of the boundary (log pi_target and the reward of every candidate from one call) returns what
+    the two specs_score_blocks calls return, bit for bit, and rejects swapped models."""
+    from paper_2506_15733_amd import synthetic, binding as B
+    wl = ragged_workload("bf16")
+    step = synthetic.ScoringStep(wl)
+    step.prefill()
+    res = step.score_and_select()
+    t, r = step.models["target"], step.models["prm"]
+    lt, rew = torch.zeros_like(step.out["target"]), torch.zeros_like(step.out["prm"])
+    tok = torch.zeros_like(step.tok["target"])
+    torch.cuda.synchronize()
+    B.specs_score_target_and_reward(t.ctx, t.model, step.prefixes["target"].handle, r.ctx, r.model,
+                                    step.prefixes["prm"].handle, step.cand, lt, rew, tok)
+    torch.cuda.synchronize()
+    assert np.array_equal(lt.cpu().numpy(), res["target"]) and np.array_equal(rew.cpu().numpy(), res["prm"])
+    assert np.array_equal(tok.cpu().numpy(), res["tok_target"])
+    with pytest.raises(B.SpecsError) as e:
+        B.specs_score_target_and_reward(r.ctx, r.model, step.prefixes["prm"].handle, t.ctx, t.model,
+                                        step.prefixes["target"].handle, step.cand, lt, rew)
+    assert e.value.code == 1
+    step.close()
+
+
 def test_invalid_arguments_are_rejected():
     from paper_2506_15733_amd import synthetic, binding as B
     wl = ragged_workload("f32")

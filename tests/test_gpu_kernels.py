@@ -185,10 +185,15 @@ def test_attention_f32_ragged(ctx):
     (14, 2, 64, 1, 2, 70, [100], 16),                # block length not a multiple of any tile
     (12, 2, 128, 2, 3, 64, [1, 17], 16),             # prefixes shorter than a key tile: one and two pages
     (8, 8, 64, 3, 2, 16, [64, 65, 127], 16),         # prefix ends on, just after and just before a tile boundary
+    (8, 8, 64, 20, 4, 32, [5, 300, 64, 64, 17, 200, 129, 1, 333, 64, 250, 90, 31, 400, 128, 77, 300, 12, 160, 222], 16),
+                                                     # 20 ragged beams with equal lengths among them: the two-phase
+                                                     # kernel deals beams to the XCDs by decreasing length
+    (8, 2, 128, 17, 5, 64, [700 - 37 * b for b in range(17)], 16),   # the same with groups of 4 and a beam count that
+                                                                     # leaves XCD slots empty
 ])
 def test_attention_bf16(ctx, Hq, Hkv, hd, Bn, n, L, lens, pt):
     d = ModelDesc("target", 1, Hq * hd, Hq, Hkv, hd, 64, 64, "bf16", "lm")
-    sample = None if Bn * n <= 8 else [0, 7, Bn * n - 1]
+    sample = None if Bn * n <= 8 else [0, 7, Bn * n - 1] if Bn < 16 else list(range(0, Bn * n, 3)) + [Bn * n - 1]
     err = attention_case(ctx, d, Bn, n, L, lens, pt, sample)
     # outputs are averages of unit normals rounded to bf16: one bf16 ulp of the largest plausible value, which is
     # below 2 when hundreds of keys are averaged and below 4 when a row sees only two or three keys

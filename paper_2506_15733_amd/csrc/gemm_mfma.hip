@@ -134,7 +134,15 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   // phase = K-tile index mod 5; the k-loop is unrolled five times so that every slot address is a constant
   auto wslot = [&](int ph) { return smem + ((2 * ph) % 5) * SLOT; };
   auto aslot = [&](int ph) { return smem + ((2 * ph + 1) % 5) * SLOT; };
+  // Measurement builds only (-DGEMM_ABLATE=bits, never defined in the library that ships): what the loop costs without
+  // one of its parts. 1: no fragment reads after the first, 2: no workgroup barrier, 4: no operand loads after the
+  // prologue. Results are wrong by construction; every access stays where it was and no wait is added.
+#ifndef GEMM_ABLATE
+#define GEMM_ABLATE 0
+#endif
+  bool in_prologue = true;
   auto read_frags = [&](int ph, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
+    if ((GEMM_ABLATE & 1) && !in_prologue) return;
     const char* As = aslot(ph);
     const char* Bs = wslot(ph);
 #pragma unroll
@@ -167,6 +175,7 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   // share SH of the loads of A-tile ta (phase pa) and W-tile tw (phase pw)
   auto issue_share = [&](int ta, int pa, int tw, int pw, auto share) {
     constexpr int SH = decltype(share)::value;
+    if ((GEMM_ABLATE & 4) && !in_prologue) return;
     const int sa = ta < KT ? ta : KT - 1, sw = tw < KT ? tw : KT - 1;   // past the end: redundant loads into free slots
 #pragma unroll
     for (int j = 0; j < NLD; ++j) {
@@ -189,6 +198,8 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
   asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");
   bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
   read_frags(0, 0, a0, b0);
+  if (GEMM_ABLATE) read_frags(0, 1, a1, b1);
+  in_prologue = false;
   auto step = [&](auto phase, int kt) {
     constexpr int P = decltype(phase)::value;
     constexpr int P1 = (P + 1) % 5, P2 = (P + 2) % 5, P3 = (P + 3) % 5;
@@ -204,7 +215,9 @@ __global__ void __launch_bounds__(128 * NWN) gemm_mfma_kernel(GemmArgs a) {
     issue_share(kt + 1, P1, kt + 2, P2, std::integral_constant<int, 3>{});
     mma(a0, b0);
     PIPE_GROUP_ORDER(S3);
-    asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (GEMM_ABLATE & 2) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
+    else if (GEMM_ABLATE & 4) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     issue_share(kt + 2, P2, kt + 3, P3, std::integral_constant<int, 0>{});
     read_frags(P1, 0, a0, b0);                         // after the last K-tile: a read of a free slot, never used
     mma(a1, b1);

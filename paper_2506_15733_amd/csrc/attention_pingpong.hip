@@ -30,6 +30,14 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
+// Measurement builds only (-DATTN_ABLATE=bits, never defined in the library that ships): the kernel without one of
+// its parts. 1: no softmax arithmetic (scores are converted to bf16 as they are), 2: no staging loads after the first
+// two tiles, 4: no fragment reads from LDS (one register value serves as every fragment). Results are wrong by
+// construction; every access that remains stays where it was and no wait is added.
+#ifndef ATTN_ABLATE
+#define ATTN_ABLATE 0
+#endif
+
 namespace {
 
 constexpr int kMaxBlockTiles = 1024;   // block tiles one workgroup can list (entries of its LDS table)
@@ -221,6 +229,7 @@ __global__ void __launch_bounds__(512, 2) attention_pingpong_kernel(PPArgs a) {
     p_off[i] = loads_keys ? (unsigned)(row * HD + k_swizzle<HD>(pg * 16 + row, slot) * 8) : (unsigned)(d * 16 + half * 8);
   }
   auto stage_part = [&](int tau, int page_id) {
+    if ((ATTN_ABLATE & 2) && tau >= 2) return;
     char* buf = smem + (tau % NSTAGE) * STAGE;
     char* dst = loads_keys ? buf + pg * 16 * KROW : buf + K_BYTES + pg * HD * 32;
     const Tile t = tile_at(tau);
@@ -279,6 +288,7 @@ __global__ void __launch_bounds__(512, 2) attention_pingpong_kernel(PPArgs a) {
       for (int r = 0; r < 16; ++r) s[hf][r] = 0.f;
     constexpr int KPF = 3;
     auto read_kf = [&](int ks, int hf) {
+      if (ATTN_ABLATE & 4) return qf[0];
       int row = hf * 32 + pi_row;
       return *(const bf16x8*)(Ks + row * KROW + (k_swizzle<HD>(row, ks * 2 + lh) << 4));
     };
@@ -306,6 +316,14 @@ __global__ void __launch_bounds__(512, 2) attention_pingpong_kernel(PPArgs a) {
 
   // softmax of tile tau: s -> pf, (m_run, l_run), rescale of o when the reference exponent moves
   auto softmax = [&](const Tile& t) {
+    if (ATTN_ABLATE & 1) {
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) pf[hf * 2 + (r >> 3)][r & 7] = (bf16_t)s[hf][r];
+      l_run = 1.f;
+      return;
+    }
     const int key_base = t.idx * 64;
     // accumulator value r of half hf in this lane is key  key_base + hf*32 + 16*(r/8) + 8*lh + r%8
     const bool need_mask = t.is_block || (key_base + 64 > P);
@@ -359,6 +377,7 @@ __global__ void __launch_bounds__(512, 2) attention_pingpong_kernel(PPArgs a) {
     const int lq = lq_c, lh = lh_c;
     constexpr int VPF = 6, NST = 4 * NI;
     auto read_vf = [&](int st) {
+      if (ATTN_ABLATE & 4) return qf[1];
       const int p4 = st / NI, dt = st % NI;
       return *(const bf16x8*)(Vs + p4 * HD * 32 + (dt * 32 + lq) * 32 + ((lh ^ ((lq >> 3) & 1)) << 4));
     };

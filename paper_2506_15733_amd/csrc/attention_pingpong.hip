@@ -286,7 +286,7 @@ __global__ void __launch_bounds__(512, 2) attention_pingpong_kernel(PPArgs a) {
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[hf][r] = 0.f;
-    constexpr int KPF = 3;
+    constexpr int KPF = 4;
     auto read_kf = [&](int ks, int hf) {
       if (ATTN_ABLATE & 4) return qf[0];
       int row = hf * 32 + pi_row;
@@ -375,7 +375,7 @@ __global__ void __launch_bounds__(512, 2) attention_pingpong_kernel(PPArgs a) {
   auto pv = [&](int tau) {
     const char* Vs = smem + (tau % NSTAGE) * STAGE + K_BYTES;
     const int lq = lq_c, lh = lh_c;
-    constexpr int VPF = 6, NST = 4 * NI;
+    constexpr int VPF = 8, NST = 4 * NI;
     auto read_vf = [&](int st) {
       if (ATTN_ABLATE & 4) return qf[1];
       const int p4 = st / NI, dt = st % NI;

@@ -120,7 +120,7 @@ def compare(res, want, dtype="f32", noise=None, stated_only=False, floor=None):
     return stats
 
 
-def check_selection(wl, res, want=None, delta_bound=None):
+def check_selection(wl, res, want=None, delta_bound=None, beams=None):
     """(1) Given the GPU's own scores the kernel's indices must equal the sequential float64 rule bit for bit.
     (2) Against the choice made from the oracle's scores: with delta = max_i |S_gpu,i - S_oracle,i| MEASURED per
     (beam, beta), every selection probability moves by a factor within exp(+-2 delta), so an index may differ only
@@ -128,6 +128,7 @@ def check_selection(wl, res, want=None, delta_bound=None):
     For eta >= 1 that band says nothing; such a (beam, beta) is counted as undetermined, and it is the caller's
     bound on the scores (compare()) that limits delta. (3) The two selection distributions are within
     tanh(delta_bound) of each other in total variation, delta_bound being the score tolerance the caller asserts.
+    beams: the beams `want` holds, in its order (default: all).
     Returns (selections that differ, undetermined ones, largest total-variation distance)."""
     u = wl.uniforms()
     idx, maxr = oracle.subsample_batch(res["target"], res["draft"], res["prm"], wl.betas, u)
@@ -135,22 +136,23 @@ def check_selection(wl, res, want=None, delta_bound=None):
     assert np.array_equal(np.asarray(maxr, dtype=np.float32), res["max_reward"])
     if want is None:
         return 0, 0, 0.0
-    oidx, _ = oracle.subsample_batch(want["target"], want["draft"], want["prm"], wl.betas, u)
+    beams = list(range(wl.B)) if beams is None else list(beams)
+    oidx, _ = oracle.subsample_batch(want["target"], want["draft"], want["prm"], wl.betas, u[beams])
     differ = undetermined = 0
     tv_max = 0.0
-    for b in range(wl.B):
+    for w, b in enumerate(beams):
         for j, beta in enumerate(wl.betas):
             s_gpu = oracle.scores(res["target"][b], res["draft"][b], res["prm"][b], beta)
-            s_or = oracle.scores(want["target"][b], want["draft"][b], want["prm"][b], beta)
+            s_or = oracle.scores(want["target"][w], want["draft"][w], want["prm"][w], beta)
             delta = float(np.abs(np.asarray(s_gpu, dtype=np.float64) - np.asarray(s_or, dtype=np.float64)).max())
             p_gpu = oracle.selection_probs(res["target"][b], res["draft"][b], res["prm"][b], beta)
-            p_or = oracle.selection_probs(want["target"][b], want["draft"][b], want["prm"][b], beta)
+            p_or = oracle.selection_probs(want["target"][w], want["draft"][w], want["prm"][w], beta)
             tv = 0.5 * float(np.abs(np.asarray(p_gpu) - np.asarray(p_or)).sum())
             tv_max = max(tv_max, tv)
             assert tv <= np.tanh(delta) + 1e-12, (b, j, tv, delta)
             if delta_bound is not None:
                 assert tv <= np.tanh(delta_bound(beta)) + 1e-12, (b, j, tv, delta_bound(beta))
-            kg, ko = int(res["idx"][b, j]), int(oidx[b][j])
+            kg, ko = int(res["idx"][b, j]), int(oidx[w][j])
             if kg == ko:
                 continue
             differ += 1
@@ -432,6 +434,8 @@ def test_c5_batched_beams_paged_ragged_prefixes():
         sub = {k: (v[beams] if k != "idx" and k != "max_reward" else v) for k, v in res.items()}
         stats = compare(sub, want, "bf16", noise)
         print(name, "beams", beams, "GPU vs oracle:", stats)
+        print(name, "selections on the stored beams (differ, undetermined, max TV):",
+              check_selection(wl, res, want, score_bound("bf16", noise), beams=beams))
     res2 = step.score_and_select()
     for k in ("target", "draft", "prm", "idx"):
         assert np.array_equal(res[k], res2[k]), k

@@ -52,7 +52,7 @@ struct PPArgs {
   bf16_t* out;          // [M][Hq*hd]
   BatchGeom g;
   int Hq, Hkv, Lp, wg_tiles, total_wg, wg_per_xcd;
-  int balanced;         // beams dealt to the XCDs by decreasing prefix length (see the kernel)
+  int balanced;         // (beam, kv head) units dealt to the XCDs by decreasing prefix length (see the kernel)
   float scale_log2e;
   int n_splits;         // > 1: the prefix tiles are cut into runs, the last run also takes the block tiles; every
   float* part_o;        //      workgroup leaves (O un-normalised, m, l) per row for the merge kernel:
@@ -91,18 +91,21 @@ __global__ void __launch_bounds__(512, 2) attention_pingpong_kernel(PPArgs a) {
   const BatchGeom& G = a.g;
   const int g = a.Hq / a.Hkv;
   // Workgroup -> (beam, kv head, row tile, run). Workgroups whose ids are congruent mod 8 share an XCD, and all
-  // workgroups of a beam go to one XCD, whose L2 then holds that beam's pages alone.
-  int b, rem;
+  // workgroups of a (beam, kv head) go to one XCD, whose L2 then fetches that head's pages once.
+  int b, kvh, rem;
   if (a.balanced) {
-    // Ragged batches: a workgroup's duration follows its beam's prefix length, so beams are dealt to the XCDs in
-    // order of decreasing length, back and forth (ranks 0..7, then 15..8, ...): every XCD gets a similar sum and
-    // starts with its longest beam. The rank -> beam look-up is recomputed by every wavefront (at most 64 beams).
-    const int per_beam = a.Hkv * a.wg_tiles * a.n_splits;
+    // Ragged batches: a workgroup's duration follows its beam's prefix length, so the (beam, kv head) units are dealt
+    // to the XCDs in order of decreasing length, back and forth (ranks 0..7, then 15..8, ...): every XCD gets the same
+    // sum to within a unit and starts with its longest ones. The rank -> beam look-up is recomputed by every
+    // wavefront (at most 64 beams).
+    const int per_unit = a.wg_tiles * a.n_splits;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int pos = slot / per_beam;
-    rem = slot - pos * per_beam;
-    const int rank = (pos & 1) ? pos * 8 + 7 - xcd : pos * 8 + xcd;
-    if (rank >= G.B) return;
+    const int pos = slot / per_unit;
+    rem = slot - pos * per_unit;
+    const int unit_rank = (pos & 1) ? pos * 8 + 7 - xcd : pos * 8 + xcd;
+    if (unit_rank >= G.B * a.Hkv) return;
+    const int rank = unit_rank / a.Hkv;
+    kvh = unit_rank - rank * a.Hkv;
     const int ln = threadIdx.x & 63;
     const int mine = ln < G.B ? G.lens[G.b0 + ln] : -1;
     int r = 0;
@@ -117,10 +120,11 @@ __global__ void __launch_bounds__(512, 2) attention_pingpong_kernel(PPArgs a) {
     if (logical >= a.total_wg) return;
     b = logical / (a.Hkv * a.wg_tiles * a.n_splits);
     rem = logical - b * (a.Hkv * a.wg_tiles * a.n_splits);
+    kvh = rem / (a.wg_tiles * a.n_splits);
+    rem -= kvh * (a.wg_tiles * a.n_splits);
   }
-  const int split = rem % a.n_splits; rem /= a.n_splits;
-  const int wg_tile = rem % a.wg_tiles;
-  const int kvh = rem / a.wg_tiles;
+  const int split = rem % a.n_splits;
+  const int wg_tile = rem / a.n_splits;
 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int grp = wave >> 2;                 // wavefronts w and w + 4 share a SIMD and belong to different groups
@@ -572,7 +576,7 @@ bool launch_attention_pingpong(const bf16_t* q, const bf16_t* kb, const bf16_t* 
   a.total_wg = base * splits;
   a.wg_per_xcd = (a.total_wg + 7) / 8;
   a.balanced = g.B >= 16 && g.B <= 64 && g.len_override < 0;
-  if (a.balanced) a.wg_per_xcd = ((g.B + 7) / 8) * md.Hkv * a.wg_tiles * splits;
+  if (a.balanced) a.wg_per_xcd = ((g.B * md.Hkv + 7) / 8) * a.wg_tiles * splits;
   if (md.hd == 128) launch_pp_variant<128>(a, s); else launch_pp_variant<64>(a, s);
   if (splits > 1) {
     dim3 grid(g.M, md.Hq);

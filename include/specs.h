@@ -6,10 +6,10 @@
  * probability proportional to exp(S_i),
  *     S_i = log(pi_target(Y_i|tr) / pi_gen(Y_i|tr)) + beta * r(Y_i|tr)               (Eq. 1).
  * Producing the three ingredients of S_i is one batched forward pass per model over the L
- * tokens of each block on top of the cached keys/values of tr (Sec. 2, "evaluating a reasoning
- * block ... computing logits of each token"; appendix "Engineering and Performance
- * Optimizations": log-probabilities only for the newly generated step, the prefix being a
- * cache hit). specs_score_blocks is that pass; specs_subsample is the selection.
+ * tokens of each block on top of the cached keys/values of tr (Sec. 2 counts the evaluation of a
+ * block, i.e. the logits of each of its tokens, as the unit of cost; the appendix on engineering
+ * and performance optimisations asks for log-probabilities of the newly generated step only, the
+ * prefix being a cache hit). specs_score_blocks is that pass; specs_subsample is the selection.
  *
  * Conventions
  *  - Every tensor pointer is a DEVICE pointer unless the comment says "host". Device memory is

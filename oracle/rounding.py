@@ -1,8 +1,8 @@
 """Operand rounding of the oracle (test infrastructure).
 
 The bf16 configurations hold weights and matrix-multiply operands in bf16 and everything else
-in wider precision ("bf16 weights and activations with fp32 accumulate" in the workload
-statement; the paper itself fixes no precision). The oracle keeps all arithmetic in float64
+in wider precision (the workload statement asks for bf16 weights and activations with float
+accumulation; the paper itself fixes no precision). The oracle keeps all arithmetic in float64
 and applies one round-to-nearest-even to bf16 at exactly the points where an operand of a
 matrix product is formed: the normalised input of a projection, Q/K/V after the rotary
 embedding, the un-normalised softmax weights (relative to a power-of-two reference) before they multiply V, the attention output,

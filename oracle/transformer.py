@@ -14,8 +14,8 @@ SwiGLU feed-forward, no biases, untied vocabulary head.
 Two modes. `block_logprobs_full` / `reward_full` recompute every candidate over all P+L
 positions with plain causal attention: that is the definition. `prefill` + `score_cached`
 keep the prefix keys/values and the last prefix hidden state and run only the L block
-positions ("only the tokens of the last step need log-probabilities", App. engineering
-notes); tests prove the two modes equal before the second is trusted at large sizes.
+positions (the appendix's engineering notes ask for log-probabilities of the last step's tokens
+only); tests prove the two modes equal before the second is trusted at large sizes.
 
 `weights` is any object with embed_rows(ids) -> [len(ids), d], layer(l) -> dict with
 wqkv [(Hq+2Hkv)*hd, d] (q heads, then k heads, then v heads), wo [d, Hq*hd], wg [F, d],

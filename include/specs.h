@@ -265,6 +265,16 @@ int specs_op_lmhead_logprob(specs_ctx* ctx, int32_t dtype, const void* A, const 
 int specs_op_attention(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, int32_t layer, const void* q,
                        const void* kb, const void* vb, int32_t n, int32_t L, void* out);
 
+/* The QKV projection of one layer with what the pass does to its result: q, k rotated by the rotary
+ * embedding at absolute position lens[b] + t (pairs (i, i + hd/2), base from the model description), all
+ * three converted to the operand dtype. A[B*n*L][d] (operand dtype) is the normalised layer input,
+ * Wqkv[(Hq+2Hkv)*hd][d] the layer's projection. Outputs (operand dtype): q[B*n*L][Hq][hd],
+ * kblk[B*n*L][Hkv][hd] and the values transposed per candidate, vT[B*n][Hkv][hd][Lp] with Lp = L rounded
+ * up to 16 and the padding zeroed: the layouts specs_op_attention's kernels read. Runs the kernels the pass
+ * runs for this shape (bf16 with more than 32 rows: the rotary embedding in the GEMM epilogue). */
+int specs_op_qkv_rope(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const void* A, const void* Wqkv,
+                      int32_t n, int32_t L, void* q, void* kblk, void* vT);
+
 const char* specs_strerror(int status);
 
 #ifdef __cplusplus

@@ -10,5 +10,5 @@ from .binding import (load_library, SpecsError, specs_workspace_bytes, specs_ctx
                       specs_score_target_and_reward, specs_commit_block,
                       specs_commit_block_dev, specs_select_and_switch, specs_path_counts,
                       specs_subsample, specs_strerror, specs_op_linear, specs_op_gate_up,
-                      specs_op_lmhead_logprob, specs_op_attention, specs_ctx_profile, specs_ctx_profile_read,
+                      specs_op_lmhead_logprob, specs_op_attention, specs_op_qkv_rope, specs_ctx_profile, specs_ctx_profile_read,
                       ModelDescC, EXPORTED_SYMBOLS)

@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = [
     "specs_model_destroy", "specs_prefix_create", "specs_prefix_destroy", "specs_prefill", "specs_score_blocks",
     "specs_commit_block", "specs_subsample", "specs_strerror", "specs_generate_blocks",
     "specs_op_linear", "specs_op_gate_up", "specs_op_lmhead_logprob", "specs_op_attention",
-    "specs_ctx_profile", "specs_ctx_profile_read", "specs_score_blocks_static", "specs_score_target_and_reward",
+    "specs_ctx_profile", "specs_ctx_profile_read", "specs_score_blocks_static", "specs_score_target_and_reward", "specs_op_qkv_rope",
     "specs_commit_block_dev", "specs_select_and_switch", "specs_path_counts",
 ]
 PATH_CLASSES = ("gemm_mfma", "gemm_skinny", "gemm_plain", "attn_mfma", "attn_plain")
@@ -82,6 +82,7 @@ def load_library():
     lib.specs_op_gate_up.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp]
     lib.specs_op_lmhead_logprob.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, vp]
     lib.specs_op_attention.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, i32, vp]
+    lib.specs_op_qkv_rope.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
     lib.specs_strerror.restype = C.c_char_p
     lib.specs_strerror.argtypes = [C.c_int]
     for name in EXPORTED_SYMBOLS:
@@ -296,6 +297,11 @@ def specs_op_lmhead_logprob(ctx, A, Wt, tok, tok_logp):
 def specs_op_attention(ctx, model, prefix, layer, q, kb, vb, n, L, out):
     _check(load_library().specs_op_attention(ctx, model, prefix, layer, _ptr(q), _ptr(kb), _ptr(vb), n, L, _ptr(out)),
            "specs_op_attention")
+
+
+def specs_op_qkv_rope(ctx, model, prefix, A, Wqkv, n, L, q, kblk, vT):
+    _check(load_library().specs_op_qkv_rope(ctx, model, prefix, _ptr(A), _ptr(Wqkv), n, L, _ptr(q), _ptr(kblk), _ptr(vT)),
+           "specs_op_qkv_rope")
 
 
 def specs_strerror(code):

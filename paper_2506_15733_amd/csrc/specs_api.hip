@@ -928,6 +928,39 @@ extern "C" int specs_op_attention(specs_ctx* ctx, const specs_model* m, const sp
   return SPECS_OK;
 }
 
+extern "C" int specs_op_qkv_rope(specs_ctx* ctx, const specs_model* m, const specs_prefix* p, const void* A,
+                                 const void* Wqkv, int32_t n, int32_t L, void* q, void* kblk, void* vT) {
+  if (!ctx || !m || !p || !A || !Wqkv || !q || !kblk || !vT || n <= 0 || L <= 0) return SPECS_EINVAL;
+  if (p->model != m || (int64_t)p->B * n * L > (int64_t)1 << 30) return SPECS_EINVAL;
+  const specs_model_desc& d = m->desc;
+  BatchGeom g = block_geom(p, n, L);
+  ModelDims md = dims_of(d);
+  const int Lp = round16(L);
+  const size_t width = (size_t)(md.Hq + 2 * md.Hkv) * md.hd;
+  const size_t cs_bytes = align256((size_t)g.M * md.hd * sizeof(float));
+  const size_t qkv_bytes = align256((size_t)g.M * width * sizeof(float));
+  if (256 + cs_bytes + qkv_bytes > ctx->workspace_bytes) return SPECS_EWORKSPACE;
+  float* cs = (float*)(ctx->workspace + 256);
+  float* qkv = (float*)(ctx->workspace + 256 + cs_bytes);
+  hipStream_t s = ctx->stream;
+  HIP_TRY(hipSetDevice(ctx->device));
+  launch_rope_table(cs, g, md.hd, md.rope_base, s);
+  if (d.dtype == SPECS_BF16) {
+    bool fused = g.M > 32 && qkv_rope_fused<bf16_t>((const bf16_t*)A, (const bf16_t*)Wqkv, cs, (bf16_t*)q, (bf16_t*)kblk,
+                                                    (bf16_t*)vT, g, md, Lp, s);
+    if (!fused) {
+      int parts = gemm_store_split<bf16_t>((const bf16_t*)A, (const bf16_t*)Wqkv, qkv, 1, g.M, (int)width, md.d, s);
+      launch_rope_split<bf16_t>(qkv, parts, cs, (bf16_t*)q, (bf16_t*)kblk, (bf16_t*)vT, g, Lp, md, s);
+    }
+  } else {
+    int parts = gemm_store_split<float>((const float*)A, (const float*)Wqkv, qkv, 1, g.M, (int)width, md.d, s);
+    launch_rope_split<float>(qkv, parts, cs, (float*)q, (float*)kblk, (float*)vT, g, Lp, md, s);
+  }
+  HIP_TRY(hipGetLastError());
+  ctx->last_model = nullptr;
+  return SPECS_OK;
+}
+
 extern "C" const char* specs_strerror(int status) {
   switch (status) {
     case SPECS_OK: return "ok";

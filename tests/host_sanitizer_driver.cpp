@@ -57,6 +57,7 @@ int main() {
   CHECK(specs_model_destroy(nullptr) == SPECS_OK && specs_prefix_destroy(nullptr) == SPECS_OK);
   CHECK(specs_score_blocks(nullptr, nullptr, nullptr, nullptr, 1, 1, nullptr, nullptr) == SPECS_EINVAL);
   CHECK(specs_score_blocks_static(nullptr, nullptr, nullptr, nullptr, 1, 1, nullptr, nullptr) == SPECS_EINVAL);
+  CHECK(specs_op_qkv_rope(nullptr, nullptr, nullptr, nullptr, nullptr, 1, 1, nullptr, nullptr, nullptr) == SPECS_EINVAL);
   CHECK(specs_score_target_and_reward(nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 1, 1, nullptr, nullptr,
                                       nullptr) == SPECS_EINVAL);
   CHECK(specs_generate_blocks(nullptr, nullptr, nullptr, 1, 1, 0, nullptr, nullptr, nullptr, nullptr) == SPECS_EINVAL);

@@ -198,3 +198,62 @@ def test_attention_bf16(ctx, Hq, Hkv, hd, Bn, n, L, lens, pt):
     # outputs are averages of unit normals rounded to bf16: one bf16 ulp of the largest plausible value, which is
     # below 2 when hundreds of keys are averaged and below 4 when a row sees only two or three keys
     assert err < 2.0 ** -7 or (min(lens) < 64 and err <= 2.0 ** -6), err
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,hd,d_model,Bn,n,L,lens", [
+    ("bf16", 28, 4, 128, 3584, 1, 4, 128, [4096]),        # 7B layer: rotary embedding inside the GEMM epilogue, head_dim 128
+    ("bf16", 6, 2, 64, 384, 3, 2, 70, [100, 17, 333]),    # head_dim 64, block length off every tile: zeroed padding of vT
+    ("bf16", 12, 2, 128, 1536, 2, 8, 2, [50, 2000]),      # 32 rows: the few-row path (projection, then the rotary kernel)
+    ("f32", 6, 2, 16, 96, 3, 3, 5, [38, 8, 20]),          # float: plain kernels
+])
+def test_qkv_projection_with_rotary_embedding(ctx, dtype, Hq, Hkv, hd, d_model, Bn, n, L, lens):
+    """q, k, v of one layer on given operands against the definition: y = A W^T in float64, q and k heads rotated
+    by oracle.rope at absolute position lens[b] + t, everything rounded once to the operand type; block keys per row,
+    block values transposed per candidate with zeroed padding. A bf16 output is the rounding of a float-accumulated
+    value: within half a unit in the last place plus the accumulation error of the exact one, and equal to the
+    oracle's rounding for all but the values that sit on a rounding boundary."""
+    from paper_2506_15733_amd import binding as B
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    M = Bn * n * L
+    width = (Hq + 2 * Hkv) * hd
+    A, tA = draw("qa", (M, d_model), 1.0, dtype)
+    Wm, tW = draw("qw", (width, d_model), 0.02, dtype)
+    page_tokens = 16 if dtype == "bf16" else 4
+    need = [(l + page_tokens - 1) // page_tokens for l in lens]
+    table = np.zeros((Bn, max(need)), np.int32)
+    cdesc = B.make_desc(1, d_model, Hq, Hkv, hd, 64, 64, dtype, "prm")
+    dummy = torch.zeros(max(d_model, 64), dtype=tdt, device=DEV)
+    ones = torch.ones(d_model, dtype=torch.float32, device=DEV)
+    layer = dict(wqkv=dummy, wo=dummy, wgu=dummy, wd=dummy, g_attn=ones, g_ffn=ones)
+    model = B.specs_model_create(ctx, cdesc, dummy, dummy, ones, [layer])
+    pool = torch.zeros((1, 2, 1, Hkv, page_tokens * hd), dtype=tdt, device=DEV)
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    h_last = torch.zeros((Bn, d_model), dtype=torch.float32, device=DEV)
+    prefix = B.specs_prefix_create(ctx, model, lens, lens_dev, page_tokens, pool, 1, torch.from_numpy(table).to(DEV), h_last)
+    Lp = (L + 15) // 16 * 16
+    q = torch.full((M, Hq, hd), 7.0, dtype=tdt, device=DEV)
+    kb = torch.full((M, Hkv, hd), 7.0, dtype=tdt, device=DEV)
+    vT = torch.full((Bn * n, Hkv, hd, Lp), 7.0, dtype=tdt, device=DEV)
+    B.specs_op_qkv_rope(ctx, model, prefix, tA, tW, n, L, q, kb, vT)
+    torch.cuda.synchronize()
+    assert B.specs_ctx_status(ctx) == 0
+    B.specs_prefix_destroy(prefix)
+    B.specs_model_destroy(model)
+    y = A.astype(np.float64) @ Wm.astype(np.float64).T
+    pos = np.concatenate([lens[b] + np.tile(np.arange(L), n) for b in range(Bn)])
+    wq = oracle.rope(y[:, :Hq * hd].reshape(M, Hq, hd), pos, 10000.0)
+    wk = oracle.rope(y[:, Hq * hd:(Hq + Hkv) * hd].reshape(M, Hkv, hd), pos, 10000.0)
+    wv = y[:, (Hq + Hkv) * hd:].reshape(Bn * n, L, Hkv, hd).transpose(0, 2, 3, 1)          # [cand][Hkv][hd][L]
+    gq, gk = q.float().cpu().numpy().astype(np.float64), kb.float().cpu().numpy().astype(np.float64)
+    gv = vT.float().cpu().numpy().astype(np.float64)
+    assert np.all(gv[..., L:] == 0.0)                                 # padding zeroed
+    for got, want in ((gq, wq), (gk, wk), (gv[..., :L], wv)):
+        if dtype == "f32":
+            assert np.abs(got - want).max() < 2e-5 * max(1.0, np.abs(want).max())
+        else:
+            # half a unit in the last place of the stored value (its rounding) plus the float accumulation error of
+            # the product, 2e-5 of the operands' scale as in the GEMM tests (a rotated pair may cancel to a value far
+            # smaller than its two terms)
+            ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.maximum(np.abs(want), np.abs(got)), 2.0 ** -30))) - 7)
+            delta = 2e-5 * np.sqrt((y ** 2).mean())
+            assert np.all(np.abs(got - want) <= 0.5 * ulp + delta), float((np.abs(got - want) - 0.5 * ulp).max())
+            assert np.mean(got == oracle.operand(want, "bf16")) > 0.99   # and nearly all values round identically
